@@ -1,0 +1,184 @@
+/*
+ * kvcomm.h - C ABI of the MI355X (gfx950) implementation of KVComm's cache-reuse step
+ * (arxiv 2510.12872, Sec. 3.4 "Anchor-based Cache Update" and the reuse branch of
+ * Algorithm 1): instead of re-prefilling a shared segment (a placeholder sample such as
+ * a peer agent's message) under a new agent-specific prefix, its base KV-cache is
+ *   1. re-positioned: keys rotated by the RoPE position delta (Sec. 3.1, "Positional
+ *      Alignment"),
+ *   2. matched against the segment's anchor pool: l2 distance of base keys, softmax of
+ *      the negative distance across anchors (Eq. "pred", Eq. "ph_update"),
+ *   3. corrected by the weighted sum of the anchors' stored key/value deviations
+ *      (Eq. "ph_update"; Eq. "pf_update" for the neighbouring prefix segment),
+ *   4. written into the agent's contiguous cache (the concatenation of workflow step 4),
+ * after which the remaining non-shared query tokens attend causally over that cache.
+ *
+ * General conventions
+ *   - All tensor data lives in DEVICE memory.  Small metadata arrays (anchor pointer
+ *     lists, anchor lengths, anchor position deltas) live in HOST memory and are read
+ *     during the call; they may be freed or changed as soon as the call returns.
+ *   - Ownership: the caller owns every buffer.  The library never allocates, frees or
+ *     keeps device memory and retains no pointer after a call returns.
+ *   - Asynchrony: a call only enqueues kernels on `stream` (a hipStream_t, passed as
+ *     void*; NULL is the default stream).  It never synchronises.  Buffers must stay
+ *     valid until the stream has passed the enqueued work.
+ *   - Errors: every entry point returns a kvcomm_status (0 = OK, negative = error).
+ *     Arguments are validated on the host before anything is enqueued; on an argument
+ *     error nothing is launched and no output is touched.  A failed launch returns
+ *     KVCOMM_EHIP.  No C++ exception crosses this boundary.
+ *   - Thread safety: no mutable global state; calls from several host threads are safe
+ *     as long as they do not write the same buffers.
+ *   - Tensors are described by kvcomm_tensor: a base pointer plus strides in ELEMENTS for
+ *     the layer, head and token axes; the channel axis (length head_dim) is contiguous.
+ *     Base pointers must be 16-byte aligned and every stride a multiple of
+ *     16 / sizeof(element) so that each row can be moved with 16-byte accesses.
+ *   - Supported: dtype f32 or bf16; head_dim in {64, 128, 256};
+ *     n_q_heads a multiple of n_kv_heads; 0 <= n_anchors <= KVCOMM_MAX_ANCHORS.
+ *     Anything else returns KVCOMM_EUNSUPPORTED.
+ */
+#ifndef KVCOMM_H
+#define KVCOMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVCOMM_MAX_ANCHORS 64
+
+typedef enum {
+    KVCOMM_OK = 0,
+    KVCOMM_EINVAL = -1,        /* null / misaligned pointer, non-positive size or temperature, bad enum */
+    KVCOMM_EUNSUPPORTED = -2,  /* valid request outside the supported shapes / dtypes */
+    KVCOMM_EWORKSPACE = -3,    /* workspace missing or smaller than the matching *_workspace() size */
+    KVCOMM_EHIP = -4           /* the HIP runtime refused a launch */
+} kvcomm_status;
+
+typedef enum { KVCOMM_F32 = 0, KVCOMM_BF16 = 1 } kvcomm_dtype;
+
+/* What the norm ||h_phi - h_psi|| of the weighting rule is reduced over, i.e. how many
+ * independent softmaxes one segment gets.  The paper's appendix on long-context anchor
+ * matching states the per-token shape [m,1,1,seq_len,1]; that is the default.        */
+typedef enum {
+    KVCOMM_W_TOKEN = 0,            /* n = seg_len;               slot j = t               */
+    KVCOMM_W_LAYER_HEAD_TOKEN = 1, /* n = L*Hkv*seg_len;         slot j = (l*Hkv+h)*S + t */
+    KVCOMM_W_SEGMENT = 2           /* n = 1 (one scalar weight per anchor, as the entropy of Eq. "pred" uses) */
+} kvcomm_wgran;
+
+typedef struct {
+    int32_t n_layers;    /* L   */
+    int32_t n_kv_heads;  /* Hkv */
+    int32_t n_q_heads;   /* Hq, a multiple of Hkv; query head hq reads kv head hq / (Hq/Hkv) */
+    int32_t head_dim;    /* D   */
+    int32_t dtype;       /* kvcomm_dtype of every cache / query / output tensor */
+    double rope_theta;   /* RoPE base: channel pair (i, i + D/2) turns by pos * theta^(-2i/D) */
+} kvcomm_model;
+
+typedef struct {
+    void *ptr;             /* device pointer to element (layer 0, head 0, token 0, channel 0) */
+    int64_t stride_layer;  /* in elements */
+    int64_t stride_head;
+    int64_t stride_token;
+} kvcomm_tensor;
+
+/* Number of weight slots n for a granularity (see kvcomm_wgran); 0 on bad arguments. */
+size_t kvcomm_weight_slots(const kvcomm_model *model, int32_t seg_len, int32_t gran);
+
+/* --------------------------------------------------------------------------------------
+ * Anchor matching: distances and weights (Eq. "pred" for the selection of anchors at
+ * least as long as the sample; Eq. "ph_update" and the weight step of Algorithm 1 for
+ *   w = softmax over anchors of  -||k_segment - k_anchor|| / temperature ).
+ *
+ *   seg_base_k     [L, Hkv, seg_len, D] base keys of the segment (base positions, unrotated).
+ *   anchor_base_k  HOST array [n_anchors] of DEVICE pointers; anchor a's base keys are laid
+ *                  out by `anchor_layout` (its ptr field is ignored) and hold anchor_len[a]
+ *                  valid tokens.  Only the first seg_len tokens of a longer anchor are read.
+ *   anchor_len     HOST array [n_anchors].  Anchor a is selected iff anchor_len[a] >= seg_len;
+ *                  unselected anchors are never read.
+ *   temperature    > 0; the paper's rule is 1.
+ *   weights_out    DEVICE [n, n_anchors] fp32 (n = kvcomm_weight_slots): selected anchors of a
+ *                  slot sum to 1, unselected anchors get exactly 0; all 0 if none is selected.
+ *   nearest_out    DEVICE [n] int32 or NULL: selected anchor of smallest distance (lowest
+ *                  index among equals), -1 if none is selected.
+ *   selected_out   DEVICE [n_anchors] int32 (0/1) or NULL.
+ *   workspace      DEVICE scratch of at least kvcomm_anchor_weights_workspace() bytes,
+ *                  256-byte aligned; contents are undefined afterwards.
+ * Distances are accumulated in double precision in a fixed order (two deterministic
+ * stages, no floating-point atomics), so results are reproducible run to run.
+ * Errors: KVCOMM_EINVAL for null/misaligned pointers, seg_len <= 0, n_anchors <= 0,
+ * temperature <= 0 or NaN, negative anchor_len, bad granularity; KVCOMM_EWORKSPACE.     */
+size_t kvcomm_anchor_weights_workspace(const kvcomm_model *model, int32_t seg_len,
+                                       int32_t n_anchors, int32_t gran);
+
+int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float temperature,
+                          kvcomm_tensor seg_base_k, int32_t seg_len,
+                          const void *const *anchor_base_k, kvcomm_tensor anchor_layout,
+                          const int32_t *anchor_len, int32_t n_anchors,
+                          float *weights_out, int32_t *nearest_out, int32_t *selected_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------------------
+ * Offset approximation fused with positional alignment (Eq. "ph_update"; with the
+ * prefix segment's tensors and the placeholder's weights it is Eq. "pf_update"):
+ *   out_k[l,h,t,:] = R(delta_pos) base_k[l,h,t,:]
+ *                    + sum_a w[j,a] * R(delta_pos - anchor_delta_pos[a]) anchor_dk[a][l,h,t,:]
+ *   out_v[l,h,t,:] =              base_v[l,h,t,:] + sum_a w[j,a] * anchor_dv[a][l,h,t,:]
+ * where R(p) is the RoPE rotation by p positions and the sums run over selected anchors
+ * (anchor_len[a] >= seg_len).  Accumulation is fp32 in anchor order after the rotated base
+ * term; bf16 outputs are rounded to nearest even once, at the store.
+ *
+ *   base_k, base_v     [L, Hkv, seg_len, D] base cache of the segment.
+ *   anchor_dk/dv       HOST arrays [n_anchors] of DEVICE pointers to the stored deviations,
+ *                      laid out by `anchor_layout` (ptr ignored), anchor_len[a] valid tokens.
+ *   weights            DEVICE [n, n_anchors] fp32 as written by kvcomm_anchor_weights.
+ *   delta_pos          new start position minus base start position of the segment.
+ *   anchor_delta_pos   HOST [n_anchors] or NULL.  Position delta at which anchor a's key
+ *                      deviation was recorded; NULL means "recorded at delta_pos", i.e. the
+ *                      deviation is added unrotated (rotate the base key, then add the offset).
+ *   out_k, out_v       [L, Hkv, seg_len, D] destination, normally a view into the agent's
+ *                      cache at the segment's token offset (so concatenation costs nothing).
+ *                      May be exactly the base tensors (in place); partial overlap is not
+ *                      allowed and is not detected.
+ * n_anchors may be 0 (pure re-positioning; weights may then be NULL).
+ * Errors: KVCOMM_EINVAL / KVCOMM_EUNSUPPORTED as above.                                  */
+int kvcomm_align_kv(const kvcomm_model *model, int32_t gran,
+                    kvcomm_tensor base_k, kvcomm_tensor base_v, int32_t seg_len,
+                    const void *const *anchor_dk, const void *const *anchor_dv,
+                    kvcomm_tensor anchor_layout, const int32_t *anchor_len, int32_t n_anchors,
+                    const float *weights, int32_t delta_pos, const int32_t *anchor_delta_pos,
+                    kvcomm_tensor out_k, kvcomm_tensor out_v, void *stream);
+
+/* --------------------------------------------------------------------------------------
+ * Causal attention of the tq non-shared suffix queries over the assembled cache (workflow
+ * step 4; q, k, v as defined in Sec. 3.1).  Suffix query i sits at cache position
+ * n_ctx + i and attends to cache tokens 0 .. n_ctx + i:
+ *   out[l,hq,i,:] = softmax_j( scale * <q[l,hq,i,:], k[l,hq/G,j,:]> ) v[l,hq/G,j,:]
+ *
+ *   q, out          [L, Hq, tq, D]; queries already carry their rotary position.
+ *   cache_k/v       [L, Hkv, n_ctx + tq, D]; the suffix tokens' own K/V are already stored at
+ *                   positions n_ctx .. n_ctx+tq-1.
+ *   softmax_scale   <= 0 selects 1/sqrt(D).
+ *   lse_out         DEVICE [L, Hq, tq] fp32 natural-log-sum-exp of the scaled scores, or NULL.
+ *   workspace       kvcomm_suffix_attn_workspace() bytes (may be 0, then NULL is accepted).
+ * bf16 tensors use bf16 MFMA with fp32 accumulation and an fp32 online softmax; f32 tensors
+ * use fp32 arithmetic throughout.
+ * Errors: KVCOMM_EINVAL for null/misaligned pointers, tq <= 0, n_ctx < 0.                */
+size_t kvcomm_suffix_attn_workspace(const kvcomm_model *model, int32_t n_ctx, int32_t tq);
+
+int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q,
+                       kvcomm_tensor cache_k, kvcomm_tensor cache_v,
+                       int32_t n_ctx, int32_t tq, float softmax_scale,
+                       kvcomm_tensor out, float *lse_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable name of a kvcomm_status; never NULL. */
+const char *kvcomm_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int kvcomm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVCOMM_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libkvcomm.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/kvcomm.h) and does
+nothing but turn torch tensors into (pointer, strides) descriptors, allocate outputs that
+the caller did not pass, and raise on a non-zero status.  All arithmetic of the reuse step
+runs inside the library's HIP kernels.  torch is used for device memory and streams only.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkvcomm.so")
+
+W_TOKEN = 0
+W_LAYER_HEAD_TOKEN = 1
+W_SEGMENT = 2
+MAX_ANCHORS = 64
+
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+
+
+class KVCommError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"libkvcomm: {message} (status {status})")
+        self.status = status
+
+
+class _CModel(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("rope_theta", ctypes.c_double)]
+
+
+class _CTensor(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("stride_layer", ctypes.c_int64), ("stride_head", ctypes.c_int64),
+                ("stride_token", ctypes.c_int64)]
+
+
+@dataclass(frozen=True)
+class Model:
+    """Shape of the model whose KV-cache is handled (kvcomm_model of the C header)."""
+    n_layers: int
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+    dtype: torch.dtype
+    rope_theta: float
+
+    def c(self):
+        if self.dtype not in _DTYPES:
+            raise KVCommError(-2, f"unsupported dtype {self.dtype}")
+        return _CModel(self.n_layers, self.n_kv_heads, self.n_q_heads, self.head_dim, _DTYPES[self.dtype],
+                       float(self.rope_theta))
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libkvcomm.so (built by paper_2510_12872_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_12872_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    mp = ctypes.POINTER(_CModel)
+    lib.kvcomm_weight_slots.argtypes = [mp, i32, i32]
+    lib.kvcomm_weight_slots.restype = sz
+    lib.kvcomm_anchor_weights_workspace.argtypes = [mp, i32, i32, i32]
+    lib.kvcomm_anchor_weights_workspace.restype = sz
+    lib.kvcomm_anchor_weights.argtypes = [mp, i32, f32, _CTensor, i32, ctypes.POINTER(vp), _CTensor,
+                                          ctypes.POINTER(i32), i32, vp, vp, vp, vp, sz, vp]
+    lib.kvcomm_anchor_weights.restype = ctypes.c_int
+    lib.kvcomm_align_kv.argtypes = [mp, i32, _CTensor, _CTensor, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                    _CTensor, ctypes.POINTER(i32), i32, vp, i32, ctypes.POINTER(i32),
+                                    _CTensor, _CTensor, vp]
+    lib.kvcomm_align_kv.restype = ctypes.c_int
+    lib.kvcomm_suffix_attn_workspace.argtypes = [mp, i32, i32]
+    lib.kvcomm_suffix_attn_workspace.restype = sz
+    lib.kvcomm_suffix_attn.argtypes = [mp, _CTensor, _CTensor, _CTensor, i32, i32, f32, _CTensor, vp, vp, sz, vp]
+    lib.kvcomm_suffix_attn.restype = ctypes.c_int
+    lib.kvcomm_status_string.argtypes = [ctypes.c_int]
+    lib.kvcomm_status_string.restype = ctypes.c_char_p
+    lib.kvcomm_version.argtypes = []
+    lib.kvcomm_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise KVCommError(status, load_library().kvcomm_status_string(status).decode())
+
+
+def _desc(t, dtype, what):
+    """[layer, head, token, channel] tensor -> kvcomm_tensor."""
+    if t.dim() != 4 or t.dtype != dtype or not t.is_cuda or t.stride(3) != 1:
+        raise KVCommError(-1, f"{what}: expected a 4-d {dtype} device tensor with contiguous channels")
+    return _CTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _anchor_args(anchors, anchor_len, dtype, what):
+    """List of same-layout anchor tensors -> (host pointer array, layout descriptor, host length array)."""
+    n = len(anchors)
+    if n == 0:
+        return None, _CTensor(None, 0, 0, 0), None
+    layout = _desc(anchors[0], dtype, what)
+    for a in anchors:
+        d = _desc(a, dtype, what)
+        if (d.stride_layer, d.stride_head, d.stride_token) != (layout.stride_layer, layout.stride_head,
+                                                               layout.stride_token):
+            raise KVCommError(-1, f"{what}: all anchors must share one layout (pad them to a common capacity)")
+    ptrs = (ctypes.c_void_p * n)(*[a.data_ptr() for a in anchors])
+    if anchor_len is None:
+        anchor_len = [a.shape[2] for a in anchors]
+    lens = (ctypes.c_int32 * n)(*[int(x) for x in anchor_len])
+    return ptrs, layout, lens
+
+
+def kvcomm_weight_slots(model, seg_len, gran=W_TOKEN):
+    return int(load_library().kvcomm_weight_slots(ctypes.byref(model.c()), seg_len, gran))
+
+
+def kvcomm_anchor_weights_workspace(model, seg_len, n_anchors, gran=W_TOKEN):
+    return int(load_library().kvcomm_anchor_weights_workspace(ctypes.byref(model.c()), seg_len, n_anchors, gran))
+
+
+def kvcomm_anchor_weights(model, seg_base_k, anchor_base_k, anchor_len=None, temperature=1.0, gran=W_TOKEN,
+                          weights_out=None, nearest_out=None, selected_out=None, workspace=None, stream=None):
+    """Anchor matching.  Returns (weights [n, A] fp32, nearest [n] int32, selected [A] int32)."""
+    lib = load_library()
+    seg_len = seg_base_k.shape[2]
+    A = len(anchor_base_k)
+    dev = seg_base_k.device
+    n = kvcomm_weight_slots(model, seg_len, gran)
+    if weights_out is None:
+        weights_out = torch.empty((n, A), dtype=torch.float32, device=dev)
+    if nearest_out is None:
+        nearest_out = torch.empty((n,), dtype=torch.int32, device=dev)
+    if selected_out is None:
+        selected_out = torch.empty((A,), dtype=torch.int32, device=dev)
+    need = kvcomm_anchor_weights_workspace(model, seg_len, A, gran)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=dev)
+    ptrs, layout, lens = _anchor_args(anchor_base_k, anchor_len, model.dtype, "anchor_base_k")
+    _check(lib.kvcomm_anchor_weights(ctypes.byref(model.c()), gran, float(temperature),
+                                     _desc(seg_base_k, model.dtype, "seg_base_k"), seg_len, ptrs, layout, lens, A,
+                                     weights_out.data_ptr(), nearest_out.data_ptr(), selected_out.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream_ptr(stream)))
+    return weights_out, nearest_out, selected_out
+
+
+def kvcomm_align_kv(model, base_k, base_v, anchor_dk, anchor_dv, weights, delta_pos, out_k, out_v,
+                    anchor_len=None, anchor_delta_pos=None, gran=W_TOKEN, stream=None):
+    """Positional alignment + offset approximation into out_k / out_v (views of the agent cache)."""
+    lib = load_library()
+    seg_len = base_k.shape[2]
+    A = len(anchor_dk)
+    if len(anchor_dv) != A:
+        raise KVCommError(-1, "anchor_dk and anchor_dv differ in length")
+    pk, layout, lens = _anchor_args(anchor_dk, anchor_len, model.dtype, "anchor_dk")
+    pv, layout_v, _ = _anchor_args(anchor_dv, anchor_len, model.dtype, "anchor_dv")
+    if A and (layout.stride_layer, layout.stride_head, layout.stride_token) != (
+            layout_v.stride_layer, layout_v.stride_head, layout_v.stride_token):
+        raise KVCommError(-1, "anchor_dk and anchor_dv must share one layout")
+    adp = None
+    if anchor_delta_pos is not None:
+        if len(anchor_delta_pos) != A:
+            raise KVCommError(-1, "anchor_delta_pos must have one entry per anchor")
+        adp = (ctypes.c_int32 * max(A, 1))(*[int(x) for x in anchor_delta_pos])
+    if A:
+        if weights is None or weights.dtype != torch.float32 or not weights.is_contiguous():
+            raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
+        if weights.numel() != kvcomm_weight_slots(model, seg_len, gran) * A:
+            raise KVCommError(-1, "weights: wrong number of elements for this granularity")
+    _check(lib.kvcomm_align_kv(ctypes.byref(model.c()), gran, _desc(base_k, model.dtype, "base_k"),
+                               _desc(base_v, model.dtype, "base_v"), seg_len, pk, pv, layout, lens, A,
+                               None if weights is None else weights.data_ptr(), int(delta_pos), adp,
+                               _desc(out_k, model.dtype, "out_k"), _desc(out_v, model.dtype, "out_v"),
+                               _stream_ptr(stream)))
+    return out_k, out_v
+
+
+def kvcomm_suffix_attn(model, q, cache_k, cache_v, n_ctx, softmax_scale=0.0, out=None, lse_out=None,
+                       want_lse=False, stream=None):
+    """Causal attention of the suffix queries q [L,Hq,Tq,D] over cache_k/v [L,Hkv,n_ctx+Tq,D]."""
+    lib = load_library()
+    tq = q.shape[2]
+    if cache_k.shape[2] != n_ctx + tq or cache_v.shape[2] != n_ctx + tq:
+        raise KVCommError(-1, "cache_k / cache_v must hold n_ctx + tq tokens")
+    if out is None:
+        out = torch.empty_like(q)
+    if want_lse and lse_out is None:
+        lse_out = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    _check(lib.kvcomm_suffix_attn(ctypes.byref(model.c()), _desc(q, model.dtype, "q"),
+                                  _desc(cache_k, model.dtype, "cache_k"), _desc(cache_v, model.dtype, "cache_v"),
+                                  int(n_ctx), tq, float(softmax_scale), _desc(out, model.dtype, "out"),
+                                  None if lse_out is None else lse_out.data_ptr(), None, 0, _stream_ptr(stream)))
+    return (out, lse_out) if want_lse else out

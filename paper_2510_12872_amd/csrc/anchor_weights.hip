@@ -1,0 +1,324 @@
+// kvcomm_anchor_weights: anchor matching.  l2 distance between the segment's base keys and
+// each selected anchor's base keys, then the softmax of the negative distance across the
+// anchor dimension (Eq. "pred", Eq. "ph_update" and the weight step of Algorithm 1; the
+// appendix on long-context anchor matching gives the reduced shape [m,1,1,seq_len,1]).
+//
+// Two deterministic stages, no floating-point atomics:
+//   1. dist_partial_kernel streams the key rows once (HBM-bound: (A+1) rows per
+//      (layer, head, token)) and leaves, per block, the squared distance of its chunk of
+//      (layer, head) pairs: partial[chunk][token][anchor] in double.
+//   2. finalize_kernel adds the chunks in index order, takes the square root and the
+//      softmax in double, and writes fp32 weights, the nearest anchor and the selection.
+// Squared differences are accumulated in double so that fp32 inputs keep ~1e-7 relative
+// accuracy in the weights and the arg-min is decided in the precision the definition uses.
+#include <math.h>
+
+#include "kvcomm_device.h"
+
+namespace {
+
+using namespace kvc;
+
+constexpr int kBlock = 256;
+constexpr int kAnchorTile = 16;  // anchors whose accumulators one lane keeps in registers
+
+struct DistPlan {
+    int lpr;            // lanes per row = D / EPV
+    int rpb;            // rows (tokens) per block
+    int n_token_tiles;
+    int lh_per_block;
+    int n_chunks;
+};
+
+DistPlan make_plan(const kvcomm_model *m, int seg_len, int gran)
+{
+    DistPlan pl;
+    const int epv = 16 / elem_size(m->dtype);
+    pl.lpr = m->head_dim / epv;
+    pl.rpb = kBlock / pl.lpr;
+    pl.n_token_tiles = (seg_len + pl.rpb - 1) / pl.rpb;
+    const int LH = m->n_layers * m->n_kv_heads;
+    if (gran == KVCOMM_W_LAYER_HEAD_TOKEN) {
+        pl.lh_per_block = 1;
+    } else {
+        const int target_blocks = 2048;
+        int n_chunks = (target_blocks + pl.n_token_tiles - 1) / pl.n_token_tiles;
+        if (n_chunks > LH) n_chunks = LH;
+        if (n_chunks < 1) n_chunks = 1;
+        pl.lh_per_block = (LH + n_chunks - 1) / n_chunks;
+    }
+    pl.n_chunks = (LH + pl.lh_per_block - 1) / pl.lh_per_block;
+    return pl;
+}
+
+struct DistParams {
+    const void *seg_k;
+    Strides s_seg, s_anc;
+    double *partial;  // [n_chunks][S][n_sel]
+    int32_t H, S, LH, n_sel, lh_per_block, n_token_tiles;
+    const void *anc[KVCOMM_MAX_ANCHORS];  // selected anchors, original order
+};
+
+// Sum of squared differences of two 16-byte vectors, added to a double accumulator.
+template <typename T>
+__device__ __forceinline__ void sqdiff_acc(double &acc, const float (&x)[Elem<T>::EPV], const u32x4 raw)
+{
+    float y[Elem<T>::EPV];
+    unpack<T>(raw, y);
+#pragma unroll
+    for (int e = 0; e < Elem<T>::EPV; ++e) {
+        const double d = (double)x[e] - (double)y[e];
+        acc = fma(d, d, acc);
+    }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr int RPB = kBlock / LPR;
+    const int tid = threadIdx.x;
+    const int row = tid / LPR, lir = tid % LPR;
+    const int tile = blockIdx.x % p.n_token_tiles;
+    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int a0 = blockIdx.y * kAnchorTile;
+    const int na = min(kAnchorTile, p.n_sel - a0);
+    const int t = tile * RPB + row;
+    const bool valid = t < p.S;
+    const int lh0 = chunk * p.lh_per_block;
+    const int lh1 = min(lh0 + p.lh_per_block, p.LH);
+
+    double acc[kAnchorTile];
+#pragma unroll
+    for (int j = 0; j < kAnchorTile; ++j) acc[j] = 0.0;
+
+    if (valid) {
+        const T *seg = static_cast<const T *>(p.seg_k);
+        for (int lh = lh0; lh < lh1; ++lh) {
+            const int l = lh / p.H, h = lh % p.H;
+            const u32x4 rs = load16_stream(seg + l * p.s_seg.layer + h * p.s_seg.head + t * p.s_seg.token + lir * EPV);
+            const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + lir * EPV;
+            u32x4 ra[kAnchorTile];
+#pragma unroll
+            for (int j = 0; j < kAnchorTile; ++j)
+                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[a0 + j]) + aoff);
+            float x[EPV];
+            unpack<T>(rs, x);
+#pragma unroll
+            for (int j = 0; j < kAnchorTile; ++j)
+                if (j < na) sqdiff_acc<T>(acc[j], x, ra[j]);
+        }
+    }
+    // Fixed-shape butterfly over the LPR lanes of a row (all inside one wavefront).
+#pragma unroll
+    for (int j = 0; j < kAnchorTile; ++j) {
+        if (j < na) {
+            double v = acc[j];
+#pragma unroll
+            for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
+            if (valid && lir == 0) p.partial[((int64_t)chunk * p.S + t) * p.n_sel + a0 + j] = v;
+        }
+    }
+}
+
+struct FinalParams {
+    const double *partial;
+    float *weights;
+    int32_t *nearest;
+    int32_t *selected_out;
+    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran;
+    double tau;
+    uint8_t col[KVCOMM_MAX_ANCHORS];   // original index of selected anchor
+    uint8_t is_sel[KVCOMM_MAX_ANCHORS];
+};
+
+// Softmax over the selected anchors of one slot, evaluated identically by each of the
+// slot's threads from the distances in `d` (LDS): every thread walks the anchors in index
+// order, so all agree bit for bit on the minimum, the arg-min and the denominator.
+__device__ __forceinline__ void slot_softmax(const FinalParams &p, const double *d, int a, int64_t slot)
+{
+    double dmin = d[0];
+    int best = 0;
+    for (int j = 1; j < p.n_sel; ++j)
+        if (d[j] < dmin) {
+            dmin = d[j];
+            best = j;
+        }
+    double denom = 0.0;
+    for (int j = 0; j < p.n_sel; ++j) denom += exp(-(d[j] - dmin) / p.tau);
+    const double w = exp(-(d[a] - dmin) / p.tau) / denom;
+    p.weights[slot * p.n_anchors + p.col[a]] = (float)w;
+    if (a == 0) {
+        if (p.nearest) p.nearest[slot] = p.col[best];
+        for (int c = 0; c < p.n_anchors; ++c)
+            if (!p.is_sel[c]) p.weights[slot * p.n_anchors + c] = 0.f;
+    }
+}
+
+// Per-token and per-(layer, head, token) granularity: thread = (slot, selected anchor).
+__global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
+{
+    __shared__ double dsh[kBlock];
+    const int tid = threadIdx.x;
+    if (blockIdx.x == 0 && p.selected_out && tid < p.n_anchors) p.selected_out[tid] = p.is_sel[tid];
+    if (p.n_sel == 0) {  // nothing selected: all weights 0, nearest -1
+        const int64_t slot = (int64_t)blockIdx.x * kBlock + tid;
+        if (slot < p.n_slots) {
+            for (int c = 0; c < p.n_anchors; ++c) p.weights[slot * p.n_anchors + c] = 0.f;
+            if (p.nearest) p.nearest[slot] = -1;
+        }
+        return;
+    }
+    const int spb = kBlock / p.n_sel;  // slots per block
+    const int sl = tid / p.n_sel, a = tid % p.n_sel;
+    const int64_t slot = (int64_t)blockIdx.x * spb + sl;
+    const bool active = sl < spb && slot < p.n_slots;
+    if (active) {
+        double s = 0.0;
+        if (p.gran == KVCOMM_W_TOKEN) {
+            for (int c = 0; c < p.n_chunks; ++c) s += p.partial[((int64_t)c * p.S + slot) * p.n_sel + a];
+        } else {
+            s = p.partial[slot * p.n_sel + a];  // one chunk per (layer, head): slot = chunk * S + t
+        }
+        dsh[sl * p.n_sel + a] = sqrt(s);
+    }
+    __syncthreads();
+    if (active) slot_softmax(p, dsh + sl * p.n_sel, a, slot);
+}
+
+// Per-segment granularity: one block; each selected anchor's partials are added by the 256
+// threads in a fixed strided order and then by a fixed LDS tree.
+__global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalParams p)
+{
+    __shared__ double red[kBlock];
+    __shared__ double dsh[KVCOMM_MAX_ANCHORS];
+    const int tid = threadIdx.x;
+    if (p.selected_out && tid < p.n_anchors) p.selected_out[tid] = p.is_sel[tid];
+    if (p.n_sel == 0) {
+        if (tid < p.n_anchors) p.weights[tid] = 0.f;
+        if (tid == 0 && p.nearest) p.nearest[0] = -1;
+        return;
+    }
+    const int64_t n = (int64_t)p.n_chunks * p.S;
+    for (int a = 0; a < p.n_sel; ++a) {
+        double s = 0.0;
+        for (int64_t i = tid; i < n; i += kBlock) s += p.partial[i * p.n_sel + a];
+        red[tid] = s;
+        __syncthreads();
+        for (int off = kBlock / 2; off >= 1; off >>= 1) {
+            if (tid < off) red[tid] += red[tid + off];
+            __syncthreads();
+        }
+        if (tid == 0) dsh[a] = sqrt(red[0]);
+        __syncthreads();
+    }
+    if (tid < p.n_sel) slot_softmax(p, dsh, tid, 0);
+}
+
+template <typename T, int LPR>
+int launch_dist(const DistParams &p, int n_blocks, hipStream_t stream)
+{
+    const int a_tiles = (p.n_sel + kAnchorTile - 1) / kAnchorTile;
+    hipLaunchKernelGGL((dist_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" size_t kvcomm_weight_slots(const kvcomm_model *model, int32_t seg_len, int32_t gran)
+{
+    if (check_model(model) || check_gran(gran) || seg_len <= 0) return 0;
+    if (gran == KVCOMM_W_TOKEN) return (size_t)seg_len;
+    if (gran == KVCOMM_W_SEGMENT) return 1;
+    return (size_t)model->n_layers * model->n_kv_heads * seg_len;
+}
+
+extern "C" size_t kvcomm_anchor_weights_workspace(const kvcomm_model *model, int32_t seg_len, int32_t n_anchors,
+                                                  int32_t gran)
+{
+    if (check_model(model) || check_gran(gran) || seg_len <= 0 || n_anchors <= 0 || n_anchors > KVCOMM_MAX_ANCHORS)
+        return 0;
+    const DistPlan pl = make_plan(model, seg_len, gran);
+    return sizeof(double) * (size_t)pl.n_chunks * seg_len * n_anchors;
+}
+
+extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float temperature,
+                                     kvcomm_tensor seg_base_k, int32_t seg_len, const void *const *anchor_base_k,
+                                     kvcomm_tensor anchor_layout, const int32_t *anchor_len, int32_t n_anchors,
+                                     float *weights_out, int32_t *nearest_out, int32_t *selected_out, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    int st = check_model(model);
+    if (st) return st;
+    if ((st = check_gran(gran))) return st;
+    if (seg_len <= 0 || n_anchors <= 0) return KVCOMM_EINVAL;
+    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
+    if (!(temperature > 0.f)) return KVCOMM_EINVAL;  // also rejects NaN
+    const int dt = model->dtype;
+    if ((st = check_tensor(seg_base_k, dt, true)) || (st = check_tensor(anchor_layout, dt, false))) return st;
+    if (!anchor_base_k || !anchor_len || !weights_out) return KVCOMM_EINVAL;
+
+    const DistPlan pl = make_plan(model, seg_len, gran);
+    DistParams dp{};
+    FinalParams fp{};
+    for (int a = 0; a < n_anchors; ++a) {
+        if (anchor_len[a] < 0) return KVCOMM_EINVAL;
+        if (anchor_len[a] < seg_len) continue;
+        if (!anchor_base_k[a] || !aligned16(anchor_base_k[a])) return KVCOMM_EINVAL;
+        fp.col[dp.n_sel] = (uint8_t)a;
+        fp.is_sel[a] = 1;
+        dp.anc[dp.n_sel++] = anchor_base_k[a];
+    }
+    const size_t need = sizeof(double) * (size_t)pl.n_chunks * seg_len * n_anchors;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return KVCOMM_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dp.seg_k = seg_base_k.ptr;
+    dp.s_seg = strides_of(seg_base_k);
+    dp.s_anc = strides_of(anchor_layout);
+    dp.partial = static_cast<double *>(workspace);
+    dp.H = model->n_kv_heads;
+    dp.S = seg_len;
+    dp.LH = model->n_layers * model->n_kv_heads;
+    dp.lh_per_block = pl.lh_per_block;
+    dp.n_token_tiles = pl.n_token_tiles;
+
+    if (dp.n_sel > 0) {
+        const int n_blocks = pl.n_chunks * pl.n_token_tiles;
+        st = KVCOMM_EUNSUPPORTED;
+        if (dt == KVCOMM_BF16) {
+            switch (pl.lpr) {
+                case 8: st = launch_dist<bf16_t, 8>(dp, n_blocks, s); break;
+                case 16: st = launch_dist<bf16_t, 16>(dp, n_blocks, s); break;
+                case 32: st = launch_dist<bf16_t, 32>(dp, n_blocks, s); break;
+            }
+        } else {
+            switch (pl.lpr) {
+                case 16: st = launch_dist<float, 16>(dp, n_blocks, s); break;
+                case 32: st = launch_dist<float, 32>(dp, n_blocks, s); break;
+                case 64: st = launch_dist<float, 64>(dp, n_blocks, s); break;
+            }
+        }
+        if (st) return st;
+    }
+
+    fp.partial = dp.partial;
+    fp.weights = weights_out;
+    fp.nearest = nearest_out;
+    fp.selected_out = selected_out;
+    fp.S = seg_len;
+    fp.n_slots = (int32_t)kvcomm_weight_slots(model, seg_len, gran);
+    fp.n_sel = dp.n_sel;
+    fp.n_anchors = n_anchors;
+    fp.n_chunks = pl.n_chunks;
+    fp.gran = gran;
+    fp.tau = (double)temperature;
+    if (gran == KVCOMM_W_SEGMENT) {
+        hipLaunchKernelGGL(finalize_segment_kernel, dim3(1), dim3(kBlock), 0, s, fp);
+    } else {
+        const int spb = dp.n_sel > 0 ? kBlock / dp.n_sel : kBlock;
+        const int n_blocks = (fp.n_slots + spb - 1) / spb;
+        hipLaunchKernelGGL(finalize_kernel, dim3(n_blocks), dim3(kBlock), 0, s, fp);
+    }
+    return launch_status();
+}

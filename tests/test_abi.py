@@ -1,0 +1,166 @@
+"""CPU-only checks of the C-ABI boundary: the built library loads without a GPU, exports every
+symbol the header declares, and turns bad arguments into status codes on the host before
+anything is enqueued (so none of these calls touches a device)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2510_12872_amd as kv
+from paper_2510_12872_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvcomm.h")
+
+EINVAL, EUNSUPPORTED, EWORKSPACE = -1, -2, -3
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(kv.library_path()):
+        from paper_2510_12872_amd import build
+        build.build()
+    return kv.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvcomm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert {"kvcomm_anchor_weights", "kvcomm_align_kv", "kvcomm_suffix_attn", "kvcomm_anchor_weights_workspace",
+            "kvcomm_suffix_attn_workspace", "kvcomm_weight_slots", "kvcomm_status_string",
+            "kvcomm_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in kvcomm.h but not exported"
+    assert lib.kvcomm_version() >= 100
+    for st in (0, -1, -2, -3, -4, 17):
+        assert lib.kvcomm_status_string(st)
+
+
+def test_header_is_plain_c(tmp_path):
+    src = tmp_path / "t.c"
+    src.write_text('#include "kvcomm.h"\nint main(void){ kvcomm_model m; (void)m; return KVCOMM_MAX_ANCHORS == 64 ? 0 : 1; }\n')
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    "-c", str(src), "-o", str(tmp_path / "t.o")], check=True)
+
+
+def _model(**kw):
+    d = dict(n_layers=2, n_kv_heads=2, n_q_heads=4, head_dim=128, dtype=1, rope_theta=5e5)
+    d.update(kw)
+    return binding._CModel(d["n_layers"], d["n_kv_heads"], d["n_q_heads"], d["head_dim"], d["dtype"], d["rope_theta"])
+
+
+def _tensor(ptr=0x1000, sl=1 << 20, sh=1 << 16, st=128):
+    return binding._CTensor(ptr, sl, sh, st)
+
+
+def _aw(lib, m, gran=0, tau=1.0, seg=None, seg_len=16, ptrs=(0x2000, 0x3000), lens=(16, 16), layout=None,
+        weights=0x4000, ws=0x10000, ws_bytes=1 << 30):
+    A = len(ptrs)
+    parr = (ctypes.c_void_p * max(A, 1))(*ptrs)
+    larr = (ctypes.c_int32 * max(A, 1))(*lens)
+    return lib.kvcomm_anchor_weights(ctypes.byref(m), gran, tau, seg or _tensor(), seg_len, parr,
+                                     layout or _tensor(None), larr, A, weights, None, None, ws, ws_bytes, None)
+
+
+def test_model_validation(lib):
+    assert _aw(lib, _model(head_dim=96)) == EUNSUPPORTED
+    assert _aw(lib, _model(head_dim=0)) == EINVAL
+    assert _aw(lib, _model(n_q_heads=3)) == EUNSUPPORTED
+    assert _aw(lib, _model(dtype=7)) == EINVAL
+    assert _aw(lib, _model(rope_theta=0.0)) == EINVAL
+    assert _aw(lib, _model(n_layers=0)) == EINVAL
+    assert lib.kvcomm_anchor_weights(None, 0, 1.0, _tensor(), 16, None, _tensor(None), None, 1, None, None, None,
+                                     None, 0, None) == EINVAL
+
+
+def test_anchor_weights_argument_errors(lib):
+    m = _model()
+    assert _aw(lib, m, tau=0.0) == EINVAL
+    assert _aw(lib, m, tau=-1.0) == EINVAL
+    assert _aw(lib, m, tau=float("nan")) == EINVAL
+    assert _aw(lib, m, gran=3) == EINVAL
+    assert _aw(lib, m, seg_len=0) == EINVAL
+    assert _aw(lib, m, ptrs=(), lens=()) == EINVAL
+    assert _aw(lib, m, ptrs=(0x2000,) * 65, lens=(16,) * 65) == EUNSUPPORTED
+    assert _aw(lib, m, seg=_tensor(ptr=None)) == EINVAL
+    assert _aw(lib, m, seg=_tensor(ptr=0x1008)) == EINVAL          # not 16-byte aligned
+    assert _aw(lib, m, seg=_tensor(st=4)) == EINVAL                # token stride not a multiple of 8 bf16
+    assert _aw(lib, m, ptrs=(0x2000, 0x3004)) == EINVAL            # misaligned selected anchor
+    assert _aw(lib, m, ptrs=(0x2000, 0)) == EINVAL                 # null selected anchor
+    assert _aw(lib, m, lens=(16, -1)) == EINVAL
+    assert _aw(lib, m, weights=None) == EINVAL
+    assert _aw(lib, m, ws=None) == EWORKSPACE
+    assert _aw(lib, m, ws=0x10010) == EWORKSPACE                   # not 256-byte aligned
+    need = lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 16, 2, 0)
+    assert need > 0
+    assert _aw(lib, m, ws_bytes=need - 1) == EWORKSPACE
+
+
+def test_workspace_and_slot_queries(lib):
+    m = _model()
+    assert lib.kvcomm_weight_slots(ctypes.byref(m), 100, 0) == 100
+    assert lib.kvcomm_weight_slots(ctypes.byref(m), 100, 1) == 2 * 2 * 100
+    assert lib.kvcomm_weight_slots(ctypes.byref(m), 100, 2) == 1
+    assert lib.kvcomm_weight_slots(ctypes.byref(m), 0, 0) == 0
+    assert lib.kvcomm_weight_slots(ctypes.byref(m), 100, 5) == 0
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 100, 0, 0) == 0
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 100, 65, 0) == 0
+    # per-(layer, head, token) weights need one partial per (layer, head)
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 100, 3, 1) == 8 * 4 * 100 * 3
+    assert lib.kvcomm_suffix_attn_workspace(ctypes.byref(m), 100, 10) == 0
+
+
+def _align(lib, m, gran=0, seg_len=16, ptrs=(0x2000,), lens=(16,), weights=0x4000, bk=None, out=None, adp=None):
+    A = len(ptrs)
+    parr = (ctypes.c_void_p * max(A, 1))(*ptrs)
+    larr = (ctypes.c_int32 * max(A, 1))(*lens)
+    aarr = None if adp is None else (ctypes.c_int32 * max(A, 1))(*adp)
+    return lib.kvcomm_align_kv(ctypes.byref(m), gran, bk or _tensor(), _tensor(0x5000), seg_len, parr, parr,
+                               _tensor(None), larr, A, weights, 64, aarr, out or _tensor(0x6000), _tensor(0x7000),
+                               None)
+
+
+def test_align_argument_errors(lib):
+    m = _model()
+    assert _align(lib, m, gran=9) == EINVAL
+    assert _align(lib, m, seg_len=-3) == EINVAL
+    assert _align(lib, m, bk=_tensor(ptr=None)) == EINVAL
+    assert _align(lib, m, out=_tensor(ptr=0x6002)) == EINVAL
+    assert _align(lib, m, weights=None) == EINVAL
+    assert _align(lib, m, ptrs=(0x2001,)) == EINVAL
+    assert _align(lib, m, ptrs=(0x2000,) * 65, lens=(16,) * 65) == EUNSUPPORTED
+    assert _align(lib, m, lens=(-5,)) == EINVAL
+    assert _align(lib, _model(head_dim=80)) == EUNSUPPORTED
+    assert _align(lib, _model(dtype=0), bk=_tensor(st=2)) == EINVAL   # fp32 rows need strides in multiples of 4
+
+
+def test_suffix_attn_argument_errors(lib):
+    m = _model()
+    call = lambda q=None, n_ctx=10, tq=4, out=None: lib.kvcomm_suffix_attn(
+        ctypes.byref(m), q or _tensor(), _tensor(0x2000), _tensor(0x3000), n_ctx, tq, 0.0, out or _tensor(0x4000),
+        None, None, 0, None)
+    assert call(tq=0) == EINVAL
+    assert call(n_ctx=-1) == EINVAL
+    assert call(q=_tensor(ptr=None)) == EINVAL
+    assert call(out=_tensor(ptr=0x4004)) == EINVAL
+    assert lib.kvcomm_suffix_attn(ctypes.byref(_model(n_q_heads=5)), _tensor(), _tensor(0x2000), _tensor(0x3000), 1, 1,
+                                  0.0, _tensor(0x4000), None, None, 0, None) == EUNSUPPORTED
+
+
+def test_binding_rejects_host_tensors_and_mixed_layouts(lib):
+    model = kv.Model(2, 2, 4, 128, torch.bfloat16, 5e5)
+    x = torch.zeros(2, 2, 16, 128, dtype=torch.bfloat16)
+    with pytest.raises(kv.KVCommError):
+        kv.kvcomm_suffix_attn(model, x, x, x, 0)
+    with pytest.raises(kv.KVCommError):
+        binding._desc(x, torch.bfloat16, "x")
+    with pytest.raises(kv.KVCommError):
+        kv.Model(2, 2, 4, 128, torch.float16, 5e5).c()
