@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVComm reuse hot path on one MI355X.
+
+A step is one pass of the whole hot path over the Llama-3-8B-shaped five-agent workload
+(workloads.LLAMA8B_5AGENTS): for each of the 5 agents, 4 peer segments of 512 tokens are
+matched against their 8-anchor pools (kvcomm_anchor_weights), re-positioned and offset-
+corrected into the agent's cache (kvcomm_align_kv), and the agent's 512 suffix queries then
+attend over the 3072-token cache (kvcomm_suffix_attn).  All inputs are synthetic, seeded and
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = aligned KV tokens per second of the whole step (alignment
+and attention); per-kernel achieved rates and roofline fractions come from HIP events recorded
+around every library call inside the same timed region.  The `cpu_baseline` object is the
+float64 oracle timed on the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, GB/s
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
+
+
+def cpu_baseline(w):
+    """Oracle (as it stands) on a bounded sample: two full segment alignments (all layers) plus the
+    attention of 6 layers of one agent; scaled to the whole workload by segment / layer / agent counts."""
+    import torch
+
+    import oracle
+    from paper_2510_12872_amd import workloads
+
+    f64 = lambda t: t.to(torch.float64).numpy()
+    n_seg = 2
+    t_align_sample = 0.0
+    for j in range(n_seg):
+        seg = workloads.make_segment(w, 0, j, "cpu")
+        args = (f64(seg.base_k), f64(seg.base_v), [f64(a) for a in seg.anchor_k],
+                [f64(a) for a in seg.anchor_dk], [f64(a) for a in seg.anchor_dv])
+        t0 = time.perf_counter()
+        oracle.reuse_step(*args, seg.delta_pos, w.rope_theta, tau=w.temperature)
+        t_align_sample += time.perf_counter() - t0
+        del seg, args
+    t_align = t_align_sample * (w.n_segments * w.n_agents / n_seg)
+
+    sl = 6                                   # layers of one agent, all q heads
+    wa = workloads.scaled(w, n_layers=sl, n_agents=1, n_segments=0, prefix_len=w.n_ctx)
+    ag = workloads.make_agent(wa, 0, "cpu")
+    q, k, v = f64(ag.q), f64(ag.cache_k), f64(ag.cache_v)
+    t0 = time.perf_counter()
+    oracle.suffix_attn(q, k, v, wa.n_ctx)
+    t_attn_sample = time.perf_counter() - t0
+    t_attn = t_attn_sample * (w.n_layers / sl) * w.n_agents
+    return {
+        "value": w.aligned_tokens / (t_align + t_attn),
+        "unit": "tokens/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": (f"{n_seg} of {w.n_agents * w.n_segments} segment alignments, all layers ({t_align_sample:.2f} s) + "
+                   f"suffix attention of {sl} of {w.n_layers} layers of one agent ({t_attn_sample:.2f} s), "
+                   f"scaled by segment / layer / agent counts"),
+        "align_tokens_per_s": w.aligned_tokens / t_align,
+        "attn_gflops": w.attn_flops() / t_attn / 1e9,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+
+    import paper_2510_12872_amd as kv
+    from paper_2510_12872_amd import hotpath, workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    kv.load_library()  # fails loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = workloads.LLAMA8B_5AGENTS
+    model = hotpath.model_of(w)
+
+    agents = [workloads.make_agent(w, a, dev) for a in range(w.n_agents)]
+    outs = [torch.empty_like(ag.q) for ag in agents]
+    scratches = [[hotpath.Scratch(model, w.seg_len, w.n_anchors, kv.W_TOKEN, dev) for _ in range(w.n_segments)]
+                 for _ in agents]
+    torch.cuda.synchronize()
+
+    ev = {"weights": [], "align": [], "attn": []}
+
+    def timed(kind, record, fn):
+        if not record:
+            fn()
+            return
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        ev[kind].append((e0, e1))
+
+    def step(record):
+        for ai, ag in enumerate(agents):
+            for j, seg in enumerate(ag.segments):
+                p0 = w.seg_offset(j)
+                sc = scratches[ai][j]
+                ok, ov = ag.cache_k[:, :, p0:p0 + w.seg_len], ag.cache_v[:, :, p0:p0 + w.seg_len]
+                timed("weights", record, lambda: kv.kvcomm_anchor_weights(
+                    model, seg.base_k, seg.anchor_k, seg.anchor_len, w.temperature, kv.W_TOKEN, sc.weights,
+                    sc.nearest, sc.selected, sc.workspace))
+                timed("align", record, lambda: kv.kvcomm_align_kv(
+                    model, seg.base_k, seg.base_v, seg.anchor_dk, seg.anchor_dv, sc.weights, seg.delta_pos, ok, ov,
+                    seg.anchor_len, seg.anchor_delta_pos))
+            timed("attn", record, lambda: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
+                                                                out=outs[ai]))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(not args.no_events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    def avg_ms(kind):
+        return sum(a.elapsed_time(b) for a, b in ev[kind]) / len(ev[kind]) if ev[kind] else None
+
+    seg_w = workloads.scaled(w, n_agents=1, n_segments=1)   # one launch = one segment
+    agent_w = workloads.scaled(w, n_agents=1)                # one attention launch = one agent
+    kernels = {}
+    t_align, t_weights, t_attn = avg_ms("align"), avg_ms("weights"), avg_ms("attn")
+    if t_align:
+        ach = seg_w.align_bytes() / (t_align * 1e-3) / 1e9
+        kernels["align_kv"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_align,
+                               "bytes_per_launch": seg_w.align_bytes(), "traffic": None}
+    if t_weights:
+        ach = seg_w.distance_bytes() / (t_weights * 1e-3) / 1e9
+        kernels["anchor_weights"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                     "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_weights,
+                                     "bytes_per_launch": seg_w.distance_bytes(), "traffic": None,
+                                     "note": "two kernels per call (partial distances + softmax finalize)"}
+    if t_attn:
+        ach = agent_w.attn_flops() / (t_attn * 1e-3) / 1e12
+        kernels["suffix_attn"] = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn,
+                                  "flops_per_launch": agent_w.attn_flops(), "traffic": None}
+    # dominant kernel = the one with the largest share of a step
+    share = {"align_kv": (t_align or 0) * w.n_agents * w.n_segments,
+             "anchor_weights": (t_weights or 0) * w.n_agents * w.n_segments,
+             "suffix_attn": (t_attn or 0) * w.n_agents}
+    dominant = max(share, key=share.get) if kernels else None
+    roofline = None
+    if dominant:
+        k = kernels[dominant]
+        roofline = {"kernel": dominant, "bound": k["bound"], "achieved": k["achieved"], "peak": k["peak"],
+                    "unit": k["unit"], "frac": k["frac"], "traffic": k["traffic"]}
+
+    result = {
+        "metric": "aligned KV tokens/s (all layers), whole reuse step: anchor weights + align + suffix attention",
+        "value": w.aligned_tokens / (elapsed / args.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_agents": w.n_agents, "segments_per_agent": w.n_segments,
+                   "seg_len": w.seg_len, "n_anchors": w.n_anchors, "n_ctx": w.n_ctx, "tq": w.tq,
+                   "layers": w.n_layers, "kv_heads": w.n_kv_heads, "q_heads": w.n_q_heads, "head_dim": w.head_dim,
+                   "aligned_tokens_per_step": w.aligned_tokens},
+        "align_tokens_per_s": (w.aligned_tokens / ((t_align + t_weights) * w.n_agents * w.n_segments * 1e-3)
+                               if t_align and t_weights else None),
+        "suffix_attn_tflops": kernels.get("suffix_attn", {}).get("achieved"),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
