@@ -44,23 +44,42 @@ constexpr int kKT = 64;  // keys per LDS tile
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <int D, int QB>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnParams p)
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// Two 8-byte transposing LDS reads (ds_read_b64_tr_b16) -> one 8 x bf16 MFMA operand.
+// Within each group of 16 lanes the instruction returns to lane i, element e, the 16-bit
+// element (i % 4) found at the address supplied by lane 4*e + i/4 of the group.
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds_byte *a1)
+{
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a1);
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int D, int QB, int WPE>
+__global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
 {
     constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T
     constexpr int NDB = D / 32;      // 32-row blocks of O^T
     constexpr int MW = 32 * QB;      // query rows per wavefront
     constexpr int BM = 4 * MW;       // query rows per block
-    constexpr int KCH = D / 8;       // 16-byte chunks per K row
-    constexpr int KPT = (kKT * KCH) / 256;          // K chunks loaded per thread
-    constexpr int VTASKS = (kKT / 4) * (D / 8);     // (4 keys x 8 channels) transposition tasks
-    constexpr int VPT = (VTASKS + 255) / 256;
+    constexpr int KCH = D / 8;       // 16-byte chunks per K / V row
+    constexpr int ROWB = D * 2;      // bytes per K / V row
+    constexpr int TILEB = kKT * ROWB;               // bytes per K (or V) tile
+    constexpr int LPT = (kKT * KCH) / 256;          // direct loads per thread and tensor
+    constexpr int KSWZ = (KCH < 16 ? KCH : 16) - 1; // K chunk swizzle: c ^ (key & KSWZ)
+    constexpr int VSWZ = KCH - 1;                   // V chunk swizzle: c ^ ((4 * (key & 3)) & VSWZ)
 
-    __shared__ u32x4 k_lds[kKT * KCH];
-    __shared__ u32x4 v_lds[D * 8];
+    // [buffer][K tile | V tile]; both tiles are [64 keys][D] with XOR-swizzled 16-byte chunks.
+    __shared__ __align__(16) unsigned char smem[2 * 2 * TILEB];
+    lds_byte *lds = (lds_byte *)smem;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, n = lane & 31, hg = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, n = lane & 31, hg = lane >> 5;
 
     // XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs;
     // give each XCD one contiguous range of logical tiles.
@@ -111,159 +130,151 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnParams p)
             for (int j = 0; j < 16; ++j) o[db][b][j] = 0.f;
     }
 
-    u32x4 kreg[KPT];
-    u32x4 vreg[VPT][4];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-    auto prefetch = [&](int tile) {
+    // ---- global -> LDS direct loads (global_load_lds_dwordx4): lane i of a wavefront fills the
+    // 16-byte LDS chunk (base + i); the swizzle is applied by choosing which global chunk it fetches.
+    // Wavefront w fills chunks [(4w + it) * 64, +64) of each tile, i.e. 64 / KCH consecutive keys.
+    int ld_key[LPT], ld_kc[LPT], ld_vc[LPT];
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+        const int P = (wave * LPT + it) * 64 + lane;
+        const int key = P / KCH, pc = P % KCH;
+        ld_key[it] = key;
+        ld_kc[it] = (pc ^ (key & KSWZ)) * 8;                    // element offset inside the row
+        ld_vc[it] = (pc ^ ((4 * (key & 3)) & VSWZ)) * 8;
+    }
+    auto issue_loads = [&](int tile, int buf) {
         const int key0 = tile * kKT;
 #pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            const int id = it * 256 + tid;
-            const int key = key0 + id / KCH, c = id % KCH;
-            kreg[it] = key < p.N ? load16(kb_ + (int64_t)key * p.s_k.token + c * 8) : zero4;
-        }
-#pragma unroll
-        for (int it = 0; it < VPT; ++it) {
-            const int id = it * 256 + tid;
-            if (id < VTASKS) {
-                const int dg = id % (D / 8), kg = id / (D / 8);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = key0 + 4 * kg + r;
-                    vreg[it][r] = key < p.N ? load16(vb_ + (int64_t)key * p.s_v.token + dg * 8) : zero4;
-                }
-            }
+        for (int it = 0; it < LPT; ++it) {
+            const int key = min(key0 + ld_key[it], p.N - 1);  // rows past the cache end are never unmasked
+            lds_byte *dk = lds + buf * 2 * TILEB + (wave * LPT + it) * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kb_ + (int64_t)key * p.s_k.token + ld_kc[it]),
+                                             (__attribute__((address_space(3))) void *)dk, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vb_ + (int64_t)key * p.s_v.token + ld_vc[it]),
+                                             (__attribute__((address_space(3))) void *)(dk + TILEB), 16, 0, 0);
         }
     };
 
-    auto stage = [&]() {
+    // ---- per-lane LDS read offsets
+    // K operand (rows = keys): lane (n, hg) reads chunk 2*ks + hg of key 32*kb + n.
+    int k_off[NKS];
 #pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            const int id = it * 256 + tid;
-            const int key = id / KCH, c = id % KCH;
-            k_lds[key * KCH + (c ^ (key & 7))] = kreg[it];
+    for (int ks = 0; ks < NKS; ++ks) k_off[ks] = n * ROWB + (((2 * ks + hg) ^ (n & KSWZ)) * 16);
+    // V^T operand through transposing reads: lane i of a 16-lane group supplies the address of
+    // 4 channels [32*db + 16*gi + 4*(i%4), +4) of key 16*ks + 4*hg + i/4 (second read: + 8 keys).
+    int v_off[NDB];
+    {
+        const int i16 = lane & 15, gi = (lane >> 4) & 1;
+        const int row = 4 * hg + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            const int col = 32 * db + 16 * gi + 4 * (i16 & 3);
+            const int pc = (col >> 3) ^ ((4 * (row & 3)) & VSWZ);
+            v_off[db] = row * ROWB + pc * 16 + (col & 7) * 2;
         }
-#pragma unroll
-        for (int it = 0; it < VPT; ++it) {
-            const int id = it * 256 + tid;
-            if (id < VTASKS) {
-                const int dg = id % (D / 8), kg = id / (D / 8);
-                const int q4 = kg & 3;                       // which 4 keys of the 16-key step
-                const int c = 2 * (kg >> 2) + (q4 & 1);      // chunk = 2 * step + lane half that reads it
-                const int sub = (q4 >> 1) * 2;               // 8-byte half of the chunk, in dwords
-                uint32_t *vl = reinterpret_cast<uint32_t *>(v_lds);
-#pragma unroll
-                for (int dd = 0; dd < 8; ++dd) {
-                    const int w = dd >> 1;
-                    uint32_t lo, hi;  // (key0, key1) and (key2, key3) of channel d
-                    if (dd & 1) {
-                        lo = (vreg[it][0][w] >> 16) | (vreg[it][1][w] & 0xffff0000u);
-                        hi = (vreg[it][2][w] >> 16) | (vreg[it][3][w] & 0xffff0000u);
-                    } else {
-                        lo = (vreg[it][0][w] & 0xffffu) | (vreg[it][1][w] << 16);
-                        hi = (vreg[it][2][w] & 0xffffu) | (vreg[it][3][w] << 16);
-                    }
-                    const int d = dg * 8 + dd;
-                    const int pc = c ^ ((d ^ (d >> 3)) & 7);
-                    u32x2 *dst = reinterpret_cast<u32x2 *>(vl + (d * 8 + pc) * 4 + sub);
-                    *dst = u32x2{lo, hi};
-                }
-            }
-        }
-    };
+    }
 
-    prefetch(0);
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 has landed in LDS
+    __syncthreads();
+
     for (int tile = 0; tile < n_tiles; ++tile) {
-        __syncthreads();  // every wavefront is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (tile + 1 < n_tiles) prefetch(tile + 1);
+        const int buf = tile & 1;
         const int key0 = tile * kKT;
-        if (key0 > wave_last_key) continue;  // wavefront-uniform: tile lies after all of its queries
+        // Tile j+1 streams into the other buffer while tile j is consumed.
+        if (tile + 1 < n_tiles) issue_loads(tile + 1, buf ^ 1);
 
-        // ---- S^T = K Q^T : [64 keys] x [MW queries]
-        f32x16 s[2][QB];
+        if (key0 <= wave_last_key) {  // wavefront-uniform: else the tile lies after all of its queries
+            const lds_byte *kl = lds + buf * 2 * TILEB;
+            const lds_byte *vl = kl + TILEB;
+
+            // ---- S^T = K Q^T : [64 keys] x [MW queries]
+            f32x16 s[2][QB];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int b = 0; b < QB; ++b)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) s[kb][b][j] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int key = kb * 32 + n;
-                const bf16x8 a = as_bf16x8(k_lds[key * KCH + ((2 * ks + hg) ^ (key & 7))]);
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int b = 0; b < QB; ++b)
-                    s[kb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b][ks], s[kb][b], 0, 0, 0);
-            }
-        }
-
-        // ---- online softmax; lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4 of each block
-        const bool need_mask = key0 + kKT - 1 > wave_nomask_key;
-        bf16x8 pf[QB][4];
 #pragma unroll
-        for (int b = 0; b < QB; ++b) {
-            if (need_mask) {
-                const int limit = p.n_ctx + qi[b] - key0;  // last visible key, relative to the tile
+                    for (int j = 0; j < 16; ++j) s[kb][b][j] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 a = as_bf16x8(*(const __attribute__((address_space(3))) u32x4 *)(kl + kb * 32 * ROWB + k_off[ks]));
+#pragma unroll
+                    for (int b = 0; b < QB; ++b)
+                        s[kb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b][ks], s[kb][b], 0, 0, 0);
+                }
+            }
+
+            // ---- online softmax; lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4 of each block
+            const bool need_mask = key0 + kKT - 1 > wave_nomask_key;
+            bf16x8 pf[QB][4];
+#pragma unroll
+            for (int b = 0; b < QB; ++b) {
+                if (need_mask) {
+                    const int limit = p.n_ctx + qi[b] - key0;  // last visible key, relative to the tile
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int key = kb * 32 + 8 * (j >> 2) + 4 * hg + (j & 3);
+                            if (key > limit) s[kb][b][j] = -INFINITY;
+                        }
+                }
+                float mx = s[0][b][0];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][b][j]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m[b], mx);  // finite: key 0 is visible to every query
+                const float mc = m_new * p.scale_log2;
+                float rs = 0.f;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
-                        const int key = kb * 32 + 8 * (j >> 2) + 4 * hg + (j & 3);
-                        if (key > limit) s[kb][b][j] = -INFINITY;
+                        const float e = __builtin_amdgcn_exp2f(s[kb][b][j] * p.scale_log2 - mc);
+                        s[kb][b][j] = e;
+                        rs += e;
                     }
-            }
-            float mx = s[0][b][0];
+                // Rescale the running sum and O only when some query of the wavefront saw a new max.
+                if (__builtin_amdgcn_ballot_w64(m_new > m[b]) != 0) {
+                    const float corr = __builtin_amdgcn_exp2f((m[b] - m_new) * p.scale_log2);
+                    lsum[b] *= corr;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][b][j]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m[b], mx);  // finite: key 0 is visible to every query
-            const float corr = __builtin_amdgcn_exp2f((m[b] - m_new) * p.scale_log2);
-            const float mc = m_new * p.scale_log2;
-            float rs = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const float e = __builtin_amdgcn_exp2f(s[kb][b][j] * p.scale_log2 - mc);
-                    s[kb][b][j] = e;
-                    rs += e;
+                        for (int j = 0; j < 16; ++j) o[db][b][j] *= corr;
                 }
-            lsum[b] = lsum[b] * corr + rs;
-            m[b] = m_new;
+                lsum[b] += rs;
+                m[b] = m_new;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+                for (int ks = 0; ks < 4; ++ks) {
+                    u32x4 pk;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) o[db][b][j] *= corr;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                u32x4 pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    pk[e] = pack_bf16x2(s[ks >> 1][b][8 * (ks & 1) + 2 * e], s[ks >> 1][b][8 * (ks & 1) + 2 * e + 1]);
-                pf[b][ks] = as_bf16x8(pk);
+                    for (int e = 0; e < 4; ++e)
+                        pk[e] = pack_bf16x2(s[ks >> 1][b][8 * (ks & 1) + 2 * e], s[ks >> 1][b][8 * (ks & 1) + 2 * e + 1]);
+                    pf[b][ks] = as_bf16x8(pk);
+                }
             }
-        }
 
-        // ---- O^T += V^T P^T : [D channels] x [MW queries]
+            // ---- O^T += V^T P^T : [D channels] x [MW queries]
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const int d = db * 32 + n;
-            const int swz = (d ^ (d >> 3)) & 7;
+            for (int db = 0; db < NDB; ++db) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 a = as_bf16x8(v_lds[d * 8 + ((2 * ks + hg) ^ swz)]);
+                for (int ks = 0; ks < 4; ++ks) {
+                    const lds_byte *va = vl + ks * 16 * ROWB + v_off[db];
+                    const bf16x8 a = lds_read_tr_pair(va, va + 8 * ROWB);
 #pragma unroll
-                for (int b = 0; b < QB; ++b)
-                    o[db][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[b][ks], o[db][b], 0, 0, 0);
+                    for (int b = 0; b < QB; ++b)
+                        o[db][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[b][ks], o[db][b], 0, 0, 0);
+                }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's share of tile j+1 is in LDS
+        __syncthreads();                     // ... and so is everybody else's; tile j is no longer read
     }
 
     // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
@@ -411,14 +422,21 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         return launch_status();
     }
 
-    constexpr int QB = 1;
+#ifndef KVC_ATTN_QB
+#define KVC_ATTN_QB 1
+#endif
+#ifndef KVC_ATTN_WPE
+#define KVC_ATTN_WPE 2
+#endif
+    constexpr int QB = KVC_ATTN_QB;
+    constexpr int WPE = KVC_ATTN_WPE;
     constexpr int BM = 4 * 32 * QB;
     p.n_row_tiles = (p.G * tq + BM - 1) / BM;
     const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
     switch (D) {
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, QB>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, QB>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, QB>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, QB, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, QB, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 1, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
         default: return KVCOMM_EUNSUPPORTED;
     }
     return launch_status();
