@@ -40,7 +40,21 @@ struct AttnParams {
 };
 
 // ------------------------------------------------------------------------------- bf16 MFMA
+#ifndef KVC_ATTN_QB
+#define KVC_ATTN_QB 1
+#endif
+#ifndef KVC_SGB_VALU
+#define KVC_SGB_VALU 7
+#endif
+#ifndef KVC_SGB_VALU2
+#define KVC_SGB_VALU2 4
+#endif
+#ifndef KVC_ATTN_WPE
+#define KVC_ATTN_WPE 2
+#endif
+
 constexpr int kKT = 64;  // keys per LDS tile
+constexpr float kLazyLog2 = 8.f;  // the softmax reference maximum lags the true one by at most 2^8
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -59,23 +73,26 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int D, int QB, int WPE>
+template <int D, int WPE>
 __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
 {
     constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T
     constexpr int NDB = D / 32;      // 32-row blocks of O^T
-    constexpr int MW = 32 * QB;      // query rows per wavefront
-    constexpr int BM = 4 * MW;       // query rows per block
+    constexpr int BM = 128;          // query rows per block: 4 wavefronts x 32
     constexpr int KCH = D / 8;       // 16-byte chunks per K / V row
     constexpr int ROWB = D * 2;      // bytes per K / V row
-    constexpr int TILEB = kKT * ROWB;               // bytes per K (or V) tile
-    constexpr int LPT = (kKT * KCH) / 256;          // direct loads per thread and tensor
+    constexpr int HALFB = 32 * ROWB; // bytes of a 32-key half tile
+    constexpr int TILEB = 64 * ROWB; // bytes of a 64-key tile
+    constexpr int RPL = 64 / KCH;    // key rows filled by one wavefront-wide direct load
+    constexpr int LPT = 16 / RPL;    // direct loads per wavefront for 16 keys ... per tensor: 64 keys / 4 waves
     constexpr int KSWZ = (KCH < 16 ? KCH : 16) - 1; // K chunk swizzle: c ^ (key & KSWZ)
     constexpr int VSWZ = KCH - 1;                   // V chunk swizzle: c ^ ((4 * (key & 3)) & VSWZ)
 
-    // [buffer][K tile | V tile]; both tiles are [64 keys][D] with XOR-swizzled 16-byte chunks.
-    __shared__ __align__(16) unsigned char smem[2 * 2 * TILEB];
-    lds_byte *lds = (lds_byte *)smem;
+    // K: ring of four 32-key halves (half h in slot h & 3); V: two 64-key tiles (tile t in buffer t & 1).
+    // Rows are [key][D] with XOR-swizzled 16-byte chunks.
+    __shared__ __align__(16) unsigned char smem[4 * HALFB + 2 * TILEB];
+    lds_byte *kring = (lds_byte *)smem;
+    lds_byte *vbuf = kring + 4 * HALFB;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -93,70 +110,91 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     const int rt = p.n_row_tiles - 1 - logical % p.n_row_tiles;  // longest rows first
     const int l = lh / p.Hkv, hkv = lh % p.Hkv;
 
-    const bf16_t *qb_ = static_cast<const bf16_t *>(p.q);
     const bf16_t *kb_ = static_cast<const bf16_t *>(p.k) + l * p.s_k.layer + hkv * p.s_k.head;
     const bf16_t *vb_ = static_cast<const bf16_t *>(p.v) + l * p.s_v.layer + hkv * p.s_v.head;
 
-    // This lane's query column in each 32-row block of the wavefront.
-    int qi[QB], qg[QB];
-    bool qvalid[QB];
-    bf16x8 qf[QB][NKS];
+    // This lane's query column: row r = i * G + g of the (layer, kv head) group.
+    const int r_row = rt * BM + wave * 32 + n;
+    const int qg = r_row % p.G;
+    const bool qvalid = r_row / p.G < p.tq;
+    const int qi = min(r_row / p.G, p.tq - 1);
+    const int hq = hkv * p.G + qg;
+    bf16x8 qf[NKS];
+    {
+        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)hq * p.s_q.head + qi * p.s_q.token;
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {
-        const int r = rt * BM + wave * MW + b * 32 + n;
-        const int i = r / p.G;
-        qg[b] = r % p.G;
-        qvalid[b] = i < p.tq;
-        qi[b] = min(i, p.tq - 1);
-        const bf16_t *qrow = qb_ + l * p.s_q.layer + (int64_t)(hkv * p.G + qg[b]) * p.s_q.head + qi[b] * p.s_q.token;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[b][ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
     }
 
+    // Every wavefront of the block walks the same tiles (one barrier per 64-key tile); the causal
+    // mask is applied from the first 32-key sub-step that is partly hidden from some query of the block.
     const int wg_imax = min(p.tq - 1, (rt * BM + BM - 1) / p.G);
-    const int n_tiles = (p.n_ctx + wg_imax + 1 + kKT - 1) / kKT;
-    const int wave_last_key = p.n_ctx + min(p.tq - 1, (rt * BM + wave * MW + MW - 1) / p.G);
-    const int wave_nomask_key = p.n_ctx + min(p.tq - 1, (rt * BM + wave * MW) / p.G);
+    const int wg_imin = min(p.tq - 1, (rt * BM) / p.G);
+    const int n_tiles = (p.n_ctx + wg_imax + 1 + 63) / 64;
+    const int n_sub = 2 * n_tiles;
+    const int sub_unmasked = (p.n_ctx + wg_imin + 1) / 32;  // sub-steps [0, sub_unmasked) are visible to all queries
 
-    f32x16 o[NDB][QB];
-    float m[QB], lsum[QB];
+    f32x16 o[NDB];
+    float m = -INFINITY, lsum = 0.f;
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {
-        m[b] = -INFINITY;
-        lsum[b] = 0.f;
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) o[db][b][j] = 0.f;
-    }
+        for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
 
     // ---- global -> LDS direct loads (global_load_lds_dwordx4): lane i of a wavefront fills the
     // 16-byte LDS chunk (base + i); the swizzle is applied by choosing which global chunk it fetches.
-    // Wavefront w fills chunks [(4w + it) * 64, +64) of each tile, i.e. 64 / KCH consecutive keys.
-    int ld_key[LPT], ld_kc[LPT], ld_vc[LPT];
+    // One instruction fills RPL consecutive key rows.  Addresses are a wavefront-uniform row pointer
+    // plus a per-lane byte offset that does not change from tile to tile.
+    // In a 64-key group, wavefront w fills keys [16w, 16w + 16); load `it` fills rows 16w + it*RPL ...
+    auto in_row_k = [&](int it) -> int {  // swizzled source chunk (bytes inside the row), K
+        const int key = it * RPL + lane / KCH;   // the row index modulo 16 is all the swizzle looks at
+        return ((lane % KCH) ^ (key & KSWZ)) * 16;
+    };
+    auto in_row_v = [&](int it) -> int {  // same for V (identical for every `it` when RPL is a multiple of 4)
+        const int key = it * RPL + lane / KCH;
+        return ((lane % KCH) ^ ((4 * (key & 3)) & VSWZ)) * 16;
+    };
+    uint32_t ld_koff[LPT], ld_voff[LPT];
 #pragma unroll
     for (int it = 0; it < LPT; ++it) {
-        const int P = (wave * LPT + it) * 64 + lane;
-        const int key = P / KCH, pc = P % KCH;
-        ld_key[it] = key;
-        ld_kc[it] = (pc ^ (key & KSWZ)) * 8;                    // element offset inside the row
-        ld_vc[it] = (pc ^ ((4 * (key & 3)) & VSWZ)) * 8;
+        ld_koff[it] = (uint32_t)((lane / KCH) * p.s_k.token * 2 + in_row_k(it));
+        ld_voff[it] = (uint32_t)((lane / KCH) * p.s_v.token * 2 + in_row_v(it));
     }
-    auto issue_loads = [&](int tile, int buf) {
-        const int key0 = tile * kKT;
+    const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kb_);
+    const unsigned char *vbytes = reinterpret_cast<const unsigned char *>(vb_);
+
+    // 64 keys starting at key0 (a multiple of 32) -> K ring; its two halves are h0 = key0/32 and h0+1.
+    // A half outside [0, n_sub) is skipped.  Wavefronts 0,1 fill the first half, 2,3 the second.
+    // `clamp` (a literal at every call site) re-reads the last row for rows past the cache end; such
+    // rows are never unmasked.  Without it the caller guarantees that all 64 rows exist.
+    auto load_k64 = [&](int key0, bool clamp) {
+        const int h = key0 / 32 + (wave >> 1);
+        if (h < 0 || h >= n_sub) return;  // wavefront-uniform
+        const int rbase = (wave & 1) * 16;
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            const int key = min(key0 + ld_key[it], p.N - 1);  // rows past the cache end are never unmasked
-            lds_byte *dk = lds + buf * 2 * TILEB + (wave * LPT + it) * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kb_ + (int64_t)key * p.s_k.token + ld_kc[it]),
-                                             (__attribute__((address_space(3))) void *)dk, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vb_ + (int64_t)key * p.s_v.token + ld_vc[it]),
-                                             (__attribute__((address_space(3))) void *)(dk + TILEB), 16, 0, 0);
+            const int row0 = 32 * h + rbase + it * RPL;  // wavefront-uniform
+            const unsigned char *src = kbytes + (int64_t)row0 * p.s_k.token * 2 + ld_koff[it];
+            if (clamp) src = kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB),
+                                             16, 0, 0);
+        }
+    };
+    auto load_v64 = [&](int tile, bool clamp) {
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const int row0 = 64 * tile + wave * 16 + it * RPL;
+            const unsigned char *src = vbytes + (int64_t)row0 * p.s_v.token * 2 + ld_voff[it];
+            if (clamp) src = vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(vbuf + (tile & 1) * TILEB + (wave * 16 + it * RPL) * ROWB),
+                                             16, 0, 0);
         }
     };
 
     // ---- per-lane LDS read offsets
-    // K operand (rows = keys): lane (n, hg) reads chunk 2*ks + hg of key 32*kb + n.
+    // K operand (rows = keys): lane (n, hg) reads chunk 2*ks + hg of key n of the half.
     int k_off[NKS];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) k_off[ks] = n * ROWB + (((2 * ks + hg) ^ (n & KSWZ)) * 16);
@@ -174,129 +212,192 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
         }
     }
 
-    issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): tile 0 has landed in LDS
-    __syncthreads();
+    // ---- phases of one 32-key sub-step u (keys [32u, 32u + 32)).
+    // The two matrix products of a step are interleaved BY HAND with the vector work that runs in
+    // their shadow: each MFMA is followed by a small chunk of independent VALU instructions and a
+    // scheduling barrier pins that order, so the matrix pipe and the vector ALU stay busy together.
+    // LDS operands are fetched two MFMAs ahead.
+    auto read_k = [&](const lds_byte *kl, int ks) -> bf16x8 {
+        return as_bf16x8(*(const __attribute__((address_space(3))) u32x4 *)(kl + k_off[ks]));
+    };
+    auto read_v = [&](const lds_byte *vl, int i) -> bf16x8 {  // i = ks * NDB + db
+        const lds_byte *va = vl + (i / NDB) * 16 * ROWB + v_off[i % NDB];
+        return lds_read_tr_pair(va, va + 8 * ROWB);
+    };
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        const int key0 = tile * kKT;
-        // Tile j+1 streams into the other buffer while tile j is consumed.
-        if (tile + 1 < n_tiles) issue_loads(tile + 1, buf ^ 1);
+    // S^T = K Q^T alone (prologue).
+    auto qk_sub = [&](int u, f32x16 &s) {
+        const lds_byte *kl = kring + (u & 3) * HALFB;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(kl, ks), qf[ks], s, 0, 0, 0);
+    };
 
-        if (key0 <= wave_last_key) {  // wavefront-uniform: else the tile lies after all of its queries
-            const lds_byte *kl = lds + buf * 2 * TILEB;
-            const lds_byte *vl = kl + TILEB;
-
-            // ---- S^T = K Q^T : [64 keys] x [MW queries]
-            f32x16 s[2][QB];
+    // Mask and running maximum of S(u) (lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4), in chunks:
+    // chunk c of NC folds elements [16c/NC, 16(c+1)/NC) into mx.
+    auto max_chunk = [&](int u, bool masked, f32x16 &s, float &mx, int c, int NC) {
+        const int limit = p.n_ctx + qi - 32 * u;  // last visible key, relative to the sub-step
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int b = 0; b < QB; ++b)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) s[kb][b][j] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 a = as_bf16x8(*(const __attribute__((address_space(3))) u32x4 *)(kl + kb * 32 * ROWB + k_off[ks]));
-#pragma unroll
-                    for (int b = 0; b < QB; ++b)
-                        s[kb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b][ks], s[kb][b], 0, 0, 0);
-                }
+        for (int j = 0; j < 16; ++j) {
+            if (j * NC / 16 != c) continue;
+            if (masked) {
+                const int key = 8 * (j >> 2) + 4 * hg + (j & 3);
+                s[j] = key > limit ? -INFINITY : s[j];
             }
-
-            // ---- online softmax; lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4 of each block
-            const bool need_mask = key0 + kKT - 1 > wave_nomask_key;
-            bf16x8 pf[QB][4];
+            mx = fmaxf(mx, s[j]);
+        }
+    };
+    // Closes the maximum: exchange with lane ^ 32 (the other 16 keys of this query) and update the
+    // REFERENCE maximum m that the exponentials are taken against.  The reference only moves when the
+    // true maximum exceeds it by more than 2^kLazyLog2 (scaled, base-2 units), so exponentials stay
+    // below 2^kLazyLog2 -- harmless in fp32 / bf16 -- and O is rescaled on very few sub-steps.  The
+    // result is mathematically the same: numerator and denominator share the reference.
+    // Returns the factor by which O has to be rescaled (exactly 1 if the reference stayed).
+    auto max_finish = [&](float mx) -> float {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        // m == -inf only before the first sub-step, where key 0 makes mx finite
+        const float m_new = (mx - m) * p.scale_log2 > kLazyLog2 ? mx : m;
+        const float corr = __builtin_amdgcn_exp2f((m - m_new) * p.scale_log2);
+        m = m_new;
+        lsum *= corr;
+        return corr;
+    };
+    // Exponentials against the reference maximum, packed bf16 B operands, and the row sum taken from
+    // the ROUNDED values (v_dot2_f32_bf16 with ones), so that numerator and denominator agree.
+    auto exp_chunk = [&](f32x16 &s, u32x4 (&pk)[2], float mc, float &rs, int c, int NC) {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-            for (int b = 0; b < QB; ++b) {
-                if (need_mask) {
-                    const int limit = p.n_ctx + qi[b] - key0;  // last visible key, relative to the tile
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) {
-                            const int key = kb * 32 + 8 * (j >> 2) + 4 * hg + (j & 3);
-                            if (key > limit) s[kb][b][j] = -INFINITY;
-                        }
-                }
-                float mx = s[0][b][0];
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][b][j]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m[b], mx);  // finite: key 0 is visible to every query
-                const float mc = m_new * p.scale_log2;
-                float rs = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const float e = __builtin_amdgcn_exp2f(s[kb][b][j] * p.scale_log2 - mc);
-                        s[kb][b][j] = e;
-                        rs += e;
-                    }
-                // Rescale the running sum and O only when some query of the wavefront saw a new max.
-                if (__builtin_amdgcn_ballot_w64(m_new > m[b]) != 0) {
-                    const float corr = __builtin_amdgcn_exp2f((m[b] - m_new) * p.scale_log2);
-                    lsum[b] *= corr;
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) o[db][b][j] *= corr;
-                }
-                lsum[b] += rs;
-                m[b] = m_new;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    u32x4 pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        pk[e] = pack_bf16x2(s[ks >> 1][b][8 * (ks & 1) + 2 * e], s[ks >> 1][b][8 * (ks & 1) + 2 * e + 1]);
-                    pf[b][ks] = as_bf16x8(pk);
-                }
-            }
-
-            // ---- O^T += V^T P^T : [D channels] x [MW queries]
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const lds_byte *va = vl + ks * 16 * ROWB + v_off[db];
-                    const bf16x8 a = lds_read_tr_pair(va, va + 8 * ROWB);
-#pragma unroll
-                    for (int b = 0; b < QB; ++b)
-                        o[db][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[b][ks], o[db][b], 0, 0, 0);
-                }
+        for (int j = 0; j < 16; ++j) {
+            if (j * NC / 16 != c) continue;
+            s[j] = __builtin_amdgcn_exp2f(s[j] * p.scale_log2 - mc);
+            if (j & 1) {
+                const uint32_t pr = pack_bf16x2(s[j - 1], s[j]);
+                pk[j >> 3][(j & 7) >> 1] = pr;
+                rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pr), ones, rs, false);
             }
         }
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's share of tile j+1 is in LDS
-        __syncthreads();                     // ... and so is everybody else's; tile j is no longer read
+    };
+    auto rescale = [&](float corr) {
+        // only when some query of the wavefront saw a new maximum (rare after the first tiles)
+        if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) o[db][j] *= corr;
+        }
+    };
+
+    // One pipeline step for sub-step u, whose scores s_a already have their maximum folded into m:
+    //   A: S(u+1) = K(u+1) Q^T on the matrix cores  ||  exponentials of S(u) on the vector ALU
+    //   B: O += V(u) P(u) on the matrix cores        ||  mask + running max of S(u+1)
+    //   C: rescale O if that maximum moved (after B, before the next sub-step is added).
+    // With has_next == false only the exponentials and the second product run.
+    auto substep = [&](int u, bool has_next, bool next_masked, f32x16 &s_a, f32x16 &s_b) {
+        u32x4 pk[2];
+        const float mc = m * p.scale_log2;
+        float rs = 0.f;
+        if (has_next) {
+            const lds_byte *kl = kring + ((u + 1) & 3) * HALFB;
+            bf16x8 ka[NKS];
+            ka[0] = read_k(kl, 0);
+            ka[1] = read_k(kl, 1);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s_b[j] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                s_b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], s_b, 0, 0, 0);
+                if (ks + 2 < NKS) ka[ks + 2] = read_k(kl, ks + 2);
+                exp_chunk(s_a, pk, mc, rs, ks, NKS);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) exp_chunk(s_a, pk, mc, rs, c, 4);
+        }
+        lsum += rs;
+        const bf16x8 pf[2] = {as_bf16x8(pk[0]), as_bf16x8(pk[1])};
+
+        const lds_byte *vl = vbuf + ((u >> 1) & 1) * TILEB + (u & 1) * HALFB;
+        constexpr int NPV = 2 * NDB;
+        bf16x8 va[NPV];
+        va[0] = read_v(vl, 0);
+        va[1] = read_v(vl, 1);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NPV; ++i) {
+            o[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[i / NDB], o[i % NDB], 0, 0, 0);
+            if (i + 2 < NPV) va[i + 2] = read_v(vl, i + 2);
+            if (has_next) max_chunk(u + 1, next_masked, s_b, mx, i, NPV);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (has_next) rescale(max_finish(mx));
+    };
+    const auto tile_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed in LDS
+        __syncthreads();                     // ... and everybody else's; what was read in this tile is free
+    };
+
+    // ---- pipeline over tiles.  During tile t the sub-steps 2t and 2t+1 read K halves 2t+1 and 2t+2
+    // and V tile t; the loads issued at its start (K halves 2t+3, 2t+4 into the slots of halves 2t-1
+    // and 2t, V tile t+1 into the buffer of tile t-1) only overwrite what tile t-1 finished reading.
+    load_k64(-32, true);  // half 0
+    load_k64(32, true);   // halves 1, 2
+    load_v64(0, true);
+    tile_barrier();
+
+    f32x16 s0, s1;
+    qk_sub(0, s0);
+    const int t_last = n_tiles - 1;
+    // Leading tiles that need no mask in either sub-step (nor in the first sub-step of the next
+    // tile, whose maximum is taken at their end) and whose look-ahead loads stay inside the cache.
+    const int t_safe = p.N >= 160 ? (p.N - 160) / 64 + 1 : 0;  // tile t loads keys up to 64t + 159
+    const int t_plain = max(0, min(min((sub_unmasked - 1) >> 1, t_last), t_safe));
+    {   // maximum of sub-step 0; O is still zero, so there is nothing to rescale
+        float mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) max_chunk(0, true, s0, mx, c, 4);
+        (void)max_finish(mx);
     }
+    int t = 0;
+    for (; t < t_plain; ++t) {
+        load_k64(64 * t + 96, false);
+        load_v64(t + 1, false);
+        substep(2 * t, true, false, s0, s1);
+        substep(2 * t + 1, true, false, s1, s0);
+        tile_barrier();
+    }
+    for (; t < t_last; ++t) {
+        load_k64(64 * t + 96, true);
+        load_v64(t + 1, true);
+        substep(2 * t, true, true, s0, s1);
+        substep(2 * t + 1, true, true, s1, s0);
+        tile_barrier();
+    }
+    substep(2 * t, true, true, s0, s1);
+    substep(2 * t + 1, false, false, s1, s0);  // the last sub-step has no successor
 
     // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
-    bf16_t *ob = static_cast<bf16_t *>(p.out);
-#pragma unroll
-    for (int b = 0; b < QB; ++b) {
-        const float ltot = lsum[b] + __shfl_xor(lsum[b], 32);
-        if (!qvalid[b]) continue;
+    float ltot;
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+        ltot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    if (qvalid) {
         const float inv = 1.f / ltot;
-        const int hq = hkv * p.G + qg[b];
-        bf16_t *orow = ob + l * p.s_o.layer + (int64_t)hq * p.s_o.head + qi[b] * p.s_o.token;
+        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq * p.s_o.head + qi * p.s_o.token;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 u32x2 w;
-                w[0] = pack_bf16x2(o[db][b][4 * j4] * inv, o[db][b][4 * j4 + 1] * inv);
-                w[1] = pack_bf16x2(o[db][b][4 * j4 + 2] * inv, o[db][b][4 * j4 + 3] * inv);
+                w[0] = pack_bf16x2(o[db][4 * j4] * inv, o[db][4 * j4 + 1] * inv);
+                w[1] = pack_bf16x2(o[db][4 * j4 + 2] * inv, o[db][4 * j4 + 3] * inv);
                 *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg) = w;
             }
         if (p.lse && hg == 0)
-            p.lse[((int64_t)l * p.Hkv * p.G + hq) * p.tq + qi[b]] = m[b] * p.scale + logf(ltot);
+            p.lse[((int64_t)l * p.Hkv * p.G + hq) * p.tq + qi] = m * p.scale + logf(ltot);
     }
 }
 
@@ -422,21 +523,14 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         return launch_status();
     }
 
-#ifndef KVC_ATTN_QB
-#define KVC_ATTN_QB 1
-#endif
-#ifndef KVC_ATTN_WPE
-#define KVC_ATTN_WPE 2
-#endif
-    constexpr int QB = KVC_ATTN_QB;
     constexpr int WPE = KVC_ATTN_WPE;
-    constexpr int BM = 4 * 32 * QB;
+    constexpr int BM = 128;
     p.n_row_tiles = (p.G * tq + BM - 1) / BM;
     const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
     switch (D) {
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, QB, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, QB, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 1, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
         default: return KVCOMM_EUNSUPPORTED;
     }
     return launch_status();
