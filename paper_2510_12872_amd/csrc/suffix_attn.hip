@@ -3,19 +3,28 @@
 // at cache position n_ctx + i and sees keys 0 .. n_ctx + i.
 //
 // bf16 path (attn_mfma_kernel): flash-style single pass on bf16 MFMA (32x32x16) with fp32
-// accumulation and an fp32 online softmax.
+// accumulation and an fp32 online softmax, written for gfx950:
 //   * GQA packing: the G query heads that share a kv head are folded into the row axis of one
 //     tile (row r = i * G + g), so each K/V tile staged in LDS serves G heads at once.
 //   * Both products are computed transposed, S^T = K Q^T and O^T = V^T P^T.  In the 32x32
-//     accumulator layout a lane then owns ONE query column: the row max and row sum of the
-//     softmax are in-register reductions plus a single exchange with lane+32, the rescale of
-//     O is a per-lane scalar, and the exponentiated scores are already laid out as the B
-//     operand of the second product (the key order inside a 16-key step is a fixed
-//     permutation, applied identically to V^T when it is written to LDS).
-//   * K tile [64 keys][D] and V^T tile [D][64 keys] live in LDS with an XOR swizzle of the
-//     16-byte chunk index so that the 16-byte operand reads are bank-conflict free; V is
-//     transposed in registers (4 keys x 8 channels per thread) on its way into LDS.
-//   * Global loads of tile j+1 are issued before the MFMA work of tile j.
+//     accumulator layout a lane then owns ONE query column: row max and row sum of the softmax
+//     are in-register reductions plus one v_permlane32_swap, the rescale of O is a per-lane
+//     scalar, and the exponentiated scores are already laid out as the B operand of the second
+//     product (the key order inside a 16-key step is a fixed permutation, matched on the V side).
+//   * K and V tiles travel global -> LDS with global_load_lds_dwordx4 (no registers, no LDS
+//     stores); the XOR swizzle of 16-byte chunks that keeps operand reads bank-conflict free is
+//     applied by choosing which global chunk each lane fetches.  K operands are read with
+//     ds_read_b128; V^T operands with ds_read_b64_tr_b16, which transposes on the way out of
+//     LDS, so V is never transposed by the vector ALU.
+//   * Work advances in 32-key sub-steps that are software pipelined inside each wavefront:
+//     while the matrix cores compute S(u+1) the vector ALU exponentiates S(u); while they
+//     accumulate O += V(u) P(u) it masks and reduces the maximum of S(u+1).  Matrix and vector
+//     instructions are interleaved by hand and pinned with scheduling barriers.
+//   * The softmax reference maximum is lazy: it only moves when the true maximum exceeds it by
+//     2^8, so O is rescaled on very few sub-steps; the row sum is taken from the bf16-rounded
+//     probabilities with v_dot2_f32_bf16.
+//   * One barrier per 64 keys; K is kept in a ring of four 32-key halves and V in two 64-key
+//     tiles so that loads run 1-2 tiles ahead of their use.
 //   * Row tiles are ordered longest-first and the block index is remapped so that the row
 //     tiles of one (layer, kv head) run on the same XCD and share its L2.
 // fp32 path (attn_f32_kernel): one wavefront per query row, plain fp32 FMA and expf with an
@@ -43,14 +52,11 @@ struct AttnParams {
 #ifndef KVC_ATTN_QB
 #define KVC_ATTN_QB 1
 #endif
-#ifndef KVC_SGB_VALU
-#define KVC_SGB_VALU 7
-#endif
-#ifndef KVC_SGB_VALU2
-#define KVC_SGB_VALU2 4
-#endif
 #ifndef KVC_ATTN_WPE
 #define KVC_ATTN_WPE 2
+#endif
+#ifndef KVC_ATTN_NW
+#define KVC_ATTN_NW 4
 #endif
 
 constexpr int kKT = 64;  // keys per LDS tile
@@ -73,18 +79,20 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int D, int WPE>
-__global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
+template <int D, int NW, int QB, int WPE>
+__global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParams p)
 {
     constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T
     constexpr int NDB = D / 32;      // 32-row blocks of O^T
-    constexpr int BM = 128;          // query rows per block: 4 wavefronts x 32
+    constexpr int MW = 32 * QB;      // query rows per wavefront: QB blocks of 32
+    constexpr int BM = MW * NW;      // query rows per block
+    constexpr int RW = 64 / NW;      // key rows of a 64-key group that one wavefront loads
     constexpr int KCH = D / 8;       // 16-byte chunks per K / V row
     constexpr int ROWB = D * 2;      // bytes per K / V row
     constexpr int HALFB = 32 * ROWB; // bytes of a 32-key half tile
     constexpr int TILEB = 64 * ROWB; // bytes of a 64-key tile
     constexpr int RPL = 64 / KCH;    // key rows filled by one wavefront-wide direct load
-    constexpr int LPT = 16 / RPL;    // direct loads per wavefront for 16 keys ... per tensor: 64 keys / 4 waves
+    constexpr int LPT = RW / RPL;    // direct loads per wavefront, tensor and 64-key group
     constexpr int KSWZ = (KCH < 16 ? KCH : 16) - 1; // K chunk swizzle: c ^ (key & KSWZ)
     constexpr int VSWZ = KCH - 1;                   // V chunk swizzle: c ^ ((4 * (key & 3)) & VSWZ)
 
@@ -113,17 +121,20 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     const bf16_t *kb_ = static_cast<const bf16_t *>(p.k) + l * p.s_k.layer + hkv * p.s_k.head;
     const bf16_t *vb_ = static_cast<const bf16_t *>(p.v) + l * p.s_v.layer + hkv * p.s_v.head;
 
-    // This lane's query column: row r = i * G + g of the (layer, kv head) group.
-    const int r_row = rt * BM + wave * 32 + n;
-    const int qg = r_row % p.G;
-    const bool qvalid = r_row / p.G < p.tq;
-    const int qi = min(r_row / p.G, p.tq - 1);
-    const int hq = hkv * p.G + qg;
-    bf16x8 qf[NKS];
-    {
-        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)hq * p.s_q.head + qi * p.s_q.token;
+    // This lane's query column in each of the wavefront's QB blocks: row r = i * G + g of the
+    // (layer, kv head) group.
+    int qi[QB], hq[QB];
+    bool qvalid[QB];
+    bf16x8 qf[QB][NKS];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
+    for (int b = 0; b < QB; ++b) {
+        const int r_row = rt * BM + wave * MW + b * 32 + n;
+        qvalid[b] = r_row / p.G < p.tq;
+        qi[b] = min(r_row / p.G, p.tq - 1);
+        hq[b] = hkv * p.G + r_row % p.G;
+        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)hq[b] * p.s_q.head + qi[b] * p.s_q.token;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[b][ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
     }
 
     // Every wavefront of the block walks the same tiles (one barrier per 64-key tile); the causal
@@ -134,24 +145,29 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     const int n_sub = 2 * n_tiles;
     const int sub_unmasked = (p.n_ctx + wg_imin + 1) / 32;  // sub-steps [0, sub_unmasked) are visible to all queries
 
-    f32x16 o[NDB];
-    float m = -INFINITY, lsum = 0.f;
+    f32x16 o[QB][NDB];
+    float m[QB], lsum[QB];
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int b = 0; b < QB; ++b) {
+        m[b] = -INFINITY;
+        lsum[b] = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[b][db][j] = 0.f;
+    }
 
     // ---- global -> LDS direct loads (global_load_lds_dwordx4): lane i of a wavefront fills the
     // 16-byte LDS chunk (base + i); the swizzle is applied by choosing which global chunk it fetches.
     // One instruction fills RPL consecutive key rows.  Addresses are a wavefront-uniform row pointer
     // plus a per-lane byte offset that does not change from tile to tile.
-    // In a 64-key group, wavefront w fills keys [16w, 16w + 16); load `it` fills rows 16w + it*RPL ...
+    // In a 64-key group, wavefront w fills keys [RW*w, RW*w + RW); load `it` fills rows RW*w + it*RPL ...
     auto in_row_k = [&](int it) -> int {  // swizzled source chunk (bytes inside the row), K
-        const int key = it * RPL + lane / KCH;   // the row index modulo 16 is all the swizzle looks at
+        const int key = wave * RW + it * RPL + lane / KCH;   // only the row index modulo 16 matters
         return ((lane % KCH) ^ (key & KSWZ)) * 16;
     };
     auto in_row_v = [&](int it) -> int {  // same for V (identical for every `it` when RPL is a multiple of 4)
-        const int key = it * RPL + lane / KCH;
+        const int key = wave * RW + it * RPL + lane / KCH;
         return ((lane % KCH) ^ ((4 * (key & 3)) & VSWZ)) * 16;
     };
     uint32_t ld_koff[LPT], ld_voff[LPT];
@@ -164,13 +180,13 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     const unsigned char *vbytes = reinterpret_cast<const unsigned char *>(vb_);
 
     // 64 keys starting at key0 (a multiple of 32) -> K ring; its two halves are h0 = key0/32 and h0+1.
-    // A half outside [0, n_sub) is skipped.  Wavefronts 0,1 fill the first half, 2,3 the second.
+    // A half outside [0, n_sub) is skipped.  The lower NW/2 wavefronts fill the first half, the rest the second.
     // `clamp` (a literal at every call site) re-reads the last row for rows past the cache end; such
     // rows are never unmasked.  Without it the caller guarantees that all 64 rows exist.
     auto load_k64 = [&](int key0, bool clamp) {
-        const int h = key0 / 32 + (wave >> 1);
+        const int h = key0 / 32 + wave / (NW / 2);
         if (h < 0 || h >= n_sub) return;  // wavefront-uniform
-        const int rbase = (wave & 1) * 16;
+        const int rbase = (wave % (NW / 2)) * RW;
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 32 * h + rbase + it * RPL;  // wavefront-uniform
@@ -184,11 +200,11 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     auto load_v64 = [&](int tile, bool clamp) {
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            const int row0 = 64 * tile + wave * 16 + it * RPL;
+            const int row0 = 64 * tile + wave * RW + it * RPL;
             const unsigned char *src = vbytes + (int64_t)row0 * p.s_v.token * 2 + ld_voff[it];
             if (clamp) src = vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(vbuf + (tile & 1) * TILEB + (wave * 16 + it * RPL) * ROWB),
+                                             (__attribute__((address_space(3))) void *)(vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB),
                                              16, 0, 0);
         }
     };
@@ -226,18 +242,24 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     };
 
     // S^T = K Q^T alone (prologue).
-    auto qk_sub = [&](int u, f32x16 &s) {
+    auto qk_sub = [&](int u, f32x16 (&s)[QB]) {
         const lds_byte *kl = kring + (u & 3) * HALFB;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+        for (int b = 0; b < QB; ++b)
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(kl, ks), qf[ks], s, 0, 0, 0);
+            for (int j = 0; j < 16; ++j) s[b][j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 a = read_k(kl, ks);
+#pragma unroll
+            for (int b = 0; b < QB; ++b) s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b][ks], s[b], 0, 0, 0);
+        }
     };
 
     // Mask and running maximum of S(u) (lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4), in chunks:
     // chunk c of NC folds elements [16c/NC, 16(c+1)/NC) into mx.
-    auto max_chunk = [&](int u, bool masked, f32x16 &s, float &mx, int c, int NC) {
-        const int limit = p.n_ctx + qi - 32 * u;  // last visible key, relative to the sub-step
+    auto max_chunk = [&](int b, int u, bool masked, f32x16 &s, float &mx, int c, int NC) {
+        const int limit = p.n_ctx + qi[b] - 32 * u;  // last visible key, relative to the sub-step
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             if (j * NC / 16 != c) continue;
@@ -254,14 +276,14 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     // below 2^kLazyLog2 -- harmless in fp32 / bf16 -- and O is rescaled on very few sub-steps.  The
     // result is mathematically the same: numerator and denominator share the reference.
     // Returns the factor by which O has to be rescaled (exactly 1 if the reference stayed).
-    auto max_finish = [&](float mx) -> float {
+    auto max_finish = [&](int b, float mx) -> float {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         // m == -inf only before the first sub-step, where key 0 makes mx finite
-        const float m_new = (mx - m) * p.scale_log2 > kLazyLog2 ? mx : m;
-        const float corr = __builtin_amdgcn_exp2f((m - m_new) * p.scale_log2);
-        m = m_new;
-        lsum *= corr;
+        const float m_new = (mx - m[b]) * p.scale_log2 > kLazyLog2 ? mx : m[b];
+        const float corr = __builtin_amdgcn_exp2f((m[b] - m_new) * p.scale_log2);
+        m[b] = m_new;
+        lsum[b] *= corr;
         return corr;
     };
     // Exponentials against the reference maximum, packed bf16 B operands, and the row sum taken from
@@ -279,13 +301,13 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
             }
         }
     };
-    auto rescale = [&](float corr) {
-        // only when some query of the wavefront saw a new maximum (rare after the first tiles)
+    auto rescale = [&](int b, float corr) {
+        // only when the reference of some query of the wavefront moved (rare after the first tiles)
         if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) o[db][j] *= corr;
+                for (int j = 0; j < 16; ++j) o[b][db][j] *= corr;
         }
     };
 
@@ -294,45 +316,70 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     //   B: O += V(u) P(u) on the matrix cores        ||  mask + running max of S(u+1)
     //   C: rescale O if that maximum moved (after B, before the next sub-step is added).
     // With has_next == false only the exponentials and the second product run.
-    auto substep = [&](int u, bool has_next, bool next_masked, f32x16 &s_a, f32x16 &s_b) {
-        u32x4 pk[2];
-        const float mc = m * p.scale_log2;
-        float rs = 0.f;
+    auto substep = [&](int u, bool has_next, bool next_masked, f32x16 (&s_a)[QB], f32x16 (&s_b)[QB]) {
+        u32x4 pk[QB][2];
+        float mc[QB], rs[QB];
+#pragma unroll
+        for (int b = 0; b < QB; ++b) {
+            mc[b] = m[b] * p.scale_log2;
+            rs[b] = 0.f;
+        }
         if (has_next) {
             const lds_byte *kl = kring + ((u + 1) & 3) * HALFB;
             bf16x8 ka[NKS];
             ka[0] = read_k(kl, 0);
             ka[1] = read_k(kl, 1);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s_b[j] = 0.f;
+            for (int b = 0; b < QB; ++b)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s_b[b][j] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                s_b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[ks], s_b, 0, 0, 0);
-                if (ks + 2 < NKS) ka[ks + 2] = read_k(kl, ks + 2);
-                exp_chunk(s_a, pk, mc, rs, ks, NKS);
-                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int b = 0; b < QB; ++b) {
+                    s_b[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[b][ks], s_b[b], 0, 0, 0);
+                    if (b == 0 && ks + 2 < NKS) ka[ks + 2] = read_k(kl, ks + 2);
+                    exp_chunk(s_a[b], pk[b], mc[b], rs[b], ks, NKS);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) exp_chunk(s_a, pk, mc, rs, c, 4);
+            for (int b = 0; b < QB; ++b)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) exp_chunk(s_a[b], pk[b], mc[b], rs[b], c, 4);
         }
-        lsum += rs;
-        const bf16x8 pf[2] = {as_bf16x8(pk[0]), as_bf16x8(pk[1])};
+        bf16x8 pf[QB][2];
+#pragma unroll
+        for (int b = 0; b < QB; ++b) {
+            lsum[b] += rs[b];
+            pf[b][0] = as_bf16x8(pk[b][0]);
+            pf[b][1] = as_bf16x8(pk[b][1]);
+        }
 
         const lds_byte *vl = vbuf + ((u >> 1) & 1) * TILEB + (u & 1) * HALFB;
         constexpr int NPV = 2 * NDB;
         bf16x8 va[NPV];
         va[0] = read_v(vl, 0);
         va[1] = read_v(vl, 1);
-        float mx = -INFINITY;
+        float mx[QB];
+#pragma unroll
+        for (int b = 0; b < QB; ++b) mx[b] = -INFINITY;
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
-            o[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[i / NDB], o[i % NDB], 0, 0, 0);
-            if (i + 2 < NPV) va[i + 2] = read_v(vl, i + 2);
-            if (has_next) max_chunk(u + 1, next_masked, s_b, mx, i, NPV);
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < QB; ++b) {
+                o[b][i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[b][i / NDB], o[b][i % NDB], 0, 0, 0);
+                if (b == 0 && i + 2 < NPV) va[i + 2] = read_v(vl, i + 2);
+                if (has_next) max_chunk(b, u + 1, next_masked, s_b[b], mx[b], i, NPV);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (has_next) rescale(max_finish(mx));
+        if (has_next) {
+#pragma unroll
+            for (int b = 0; b < QB; ++b) rescale(b, max_finish(b, mx[b]));
+        }
+
     };
     const auto tile_barrier = [&]() {
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed in LDS
@@ -347,18 +394,19 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     load_v64(0, true);
     tile_barrier();
 
-    f32x16 s0, s1;
+    f32x16 s0[QB], s1[QB];
     qk_sub(0, s0);
     const int t_last = n_tiles - 1;
     // Leading tiles that need no mask in either sub-step (nor in the first sub-step of the next
     // tile, whose maximum is taken at their end) and whose look-ahead loads stay inside the cache.
     const int t_safe = p.N >= 160 ? (p.N - 160) / 64 + 1 : 0;  // tile t loads keys up to 64t + 159
     const int t_plain = max(0, min(min((sub_unmasked - 1) >> 1, t_last), t_safe));
-    {   // maximum of sub-step 0; O is still zero, so there is nothing to rescale
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {  // maximum of sub-step 0; O is still zero, so there is nothing to rescale
         float mx = -INFINITY;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) max_chunk(0, true, s0, mx, c, 4);
-        (void)max_finish(mx);
+        for (int c = 0; c < 4; ++c) max_chunk(b, 0, true, s0[b], mx, c, 4);
+        (void)max_finish(b, mx);
     }
     int t = 0;
     for (; t < t_plain; ++t) {
@@ -379,25 +427,27 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const AttnParams p)
     substep(2 * t + 1, false, false, s1, s0);  // the last sub-step has no successor
 
     // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
-    float ltot;
-    {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
-        ltot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-    }
-    if (qvalid) {
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        float ltot;
+        {
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum[b]), __float_as_uint(lsum[b]), false, false);
+            ltot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        }
+        if (!qvalid[b]) continue;
         const float inv = 1.f / ltot;
-        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq * p.s_o.head + qi * p.s_o.token;
+        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq[b] * p.s_o.head + qi[b] * p.s_o.token;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 u32x2 w;
-                w[0] = pack_bf16x2(o[db][4 * j4] * inv, o[db][4 * j4 + 1] * inv);
-                w[1] = pack_bf16x2(o[db][4 * j4 + 2] * inv, o[db][4 * j4 + 3] * inv);
+                w[0] = pack_bf16x2(o[b][db][4 * j4] * inv, o[b][db][4 * j4 + 1] * inv);
+                w[1] = pack_bf16x2(o[b][db][4 * j4 + 2] * inv, o[b][db][4 * j4 + 3] * inv);
                 *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg) = w;
             }
         if (p.lse && hg == 0)
-            p.lse[((int64_t)l * p.Hkv * p.G + hq) * p.tq + qi] = m * p.scale + logf(ltot);
+            p.lse[((int64_t)l * p.Hkv * p.G + hq[b]) * p.tq + qi[b]] = m[b] * p.scale + logf(ltot);
     }
 }
 
@@ -523,14 +573,16 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         return launch_status();
     }
 
-    constexpr int WPE = KVC_ATTN_WPE;
-    constexpr int BM = 128;
-    p.n_row_tiles = (p.G * tq + BM - 1) / BM;
+    constexpr int NW = KVC_ATTN_NW;    // wavefronts per block
+    constexpr int QB = KVC_ATTN_QB;    // 32-query blocks per wavefront
+    constexpr int WPE = KVC_ATTN_WPE;  // wavefronts per SIMD the register budget is sized for
+    const int bm = D == 256 ? 128 : 32 * NW * QB;
+    p.n_row_tiles = (p.G * tq + bm - 1) / bm;
     const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
     switch (D) {
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, WPE>), dim3(n_blocks), dim3(256), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, NW, QB, WPE>), dim3(n_blocks), dim3(64 * NW), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, NW, QB, WPE>), dim3(n_blocks), dim3(64 * NW), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 4, 1, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
         default: return KVCOMM_EUNSUPPORTED;
     }
     return launch_status();
