@@ -10,9 +10,13 @@
 // vector).  Lane r of a row owns channels [r*EPV, r*EPV+EPV) of the first half and the
 // same channels of the second half, i.e. both members of each RoPE pair (i, i + D/2), so
 // the rotation needs no cross-lane traffic and the kernel may run in place.  A block of
-// 256 threads owns a tile of 256/LPR consecutive tokens and walks over a chunk of
-// (layer, head) pairs; its per-token anchor weights and the cos/sin tables therefore
-// load once per block (LDS) and every access to a tensor is a run of whole 128-byte lines.
+// 256 threads owns a tile of 256/LPR consecutive tokens of one (layer, head) and of ONE of
+// the two tensors (blockIdx.y: 0 = keys, 1 = values): the two streams are independent, and
+// splitting them halves the registers per lane so that many wavefronts per CU keep loads in
+// flight.  Every access to a tensor is a run of whole 128-byte lines; the traffic is marked
+// non-temporal.  Per-token anchor weights and the cos/sin tables load once per block (LDS).
+// cos/sin: the angle delta * theta^(-2i/D) is formed and reduced modulo 2*pi in double from a
+// host-computed frequency table (kernel argument); sine and cosine of the reduced angle are fp32.
 #include <math.h>
 
 #include "kvcomm_device.h"
@@ -23,11 +27,12 @@ using namespace kvc;
 
 constexpr int kBlock = 256;
 constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
+constexpr int kMaxHalf = 128;  // head_dim / 2 for the largest supported head_dim
 
 struct AlignParams {
-    const void *base_k, *base_v;
-    void *out_k, *out_v;
-    Strides s_bk, s_bv, s_ok, s_ov, s_anc;
+    const void *base[2];   // [0] keys, [1] values
+    void *out[2];
+    Strides s_base[2], s_out[2], s_anc;
     const float *weights;
     int32_t H, S, LH;          // kv heads, tokens, layers*heads
     int32_t w_pitch;           // anchors per weight row (n_anchors of the call)
@@ -36,12 +41,11 @@ struct AlignParams {
     int32_t lh_per_block, n_token_tiles;
     int32_t n_tab;             // rotation tables built per block
     int32_t base_tab;          // table of the base keys' rotation + 1, 0 = identity
-    double log2_theta;
     int32_t tab_delta[kMaxTab];                 // position delta of each table
-    const void *dk[KVCOMM_MAX_ANCHORS];         // selected anchors, original order
-    const void *dv[KVCOMM_MAX_ANCHORS];
+    const void *anc[2][KVCOMM_MAX_ANCHORS];     // [0] dK, [1] dV of the selected anchors, original order
     uint8_t col[KVCOMM_MAX_ANCHORS];            // weight column of selected anchor
     uint8_t tab[KVCOMM_MAX_ANCHORS];            // its rotation table + 1, 0 = identity
+    double inv_freq[kMaxHalf];                  // theta^(-2i/D), i < D/2
 };
 
 template <typename T, int LPR>
@@ -60,18 +64,24 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
     const int lir = tid % LPR;
     const int tile = blockIdx.x % p.n_token_tiles;
     const int chunk = blockIdx.x / p.n_token_tiles;
+    const int which = blockIdx.y;          // 0 = keys (rotated), 1 = values
+    const bool is_k = which == 0;
     const int t = tile * RPB + row;
     const bool valid = t < p.S;
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
-    // cos/sin of delta * theta^(-2i/D): angle and reduction in double, stored as fp32.
-    for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock) {
-        const int r = idx / HALF, i = idx % HALF;
-        const double freq = exp2(-((double)i / (double)HALF) * p.log2_theta);
-        double s, c;
-        sincos((double)p.tab_delta[r] * freq, &s, &c);
-        cs[idx] = make_float2((float)c, (float)s);
+    if (is_k) {
+        // cos/sin of delta * theta^(-2i/D): product and reduction modulo 2*pi in double.
+        for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock) {
+            const int r = idx / HALF, i = idx % HALF;
+            const double x = (double)p.tab_delta[r] * p.inv_freq[i];
+            const double k = rint(x * 0.15915494309189535);               // 1 / (2 pi)
+            double red = fma(-k, 6.283185307179586, x);                   // 2 pi, high part
+            red = fma(-k, 2.4492935982947064e-16, red);                   // 2 pi, low part
+            const float rf = (float)red;
+            cs[idx] = make_float2(cosf(rf), sinf(rf));
+        }
     }
     if (p.gran != KVCOMM_W_LAYER_HEAD_TOKEN) {
         for (int idx = tid; idx < RPB * p.n_sel; idx += kBlock) {
@@ -84,8 +94,9 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
     __syncthreads();
     if (!valid) return;
 
+    const bool rot_base = is_k && p.base_tab != 0;
     float bc[EPV], bs[EPV];
-    if (p.base_tab) {
+    if (rot_base) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
             const float2 v = cs[(p.base_tab - 1) * HALF + lir * EPV + e];
@@ -94,89 +105,77 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
         }
     }
 
-    const T *bk = static_cast<const T *>(p.base_k);
-    const T *bv = static_cast<const T *>(p.base_v);
-    T *ok = static_cast<T *>(p.out_k);
-    T *ov = static_cast<T *>(p.out_v);
+    const T *bp = static_cast<const T *>(p.base[which]);
+    T *op = static_cast<T *>(p.out[which]);
+    const Strides sb = p.s_base[which], so = p.s_out[which];
     const int64_t col0 = (int64_t)lir * EPV;
 
     for (int lh = lh0; lh < lh1; ++lh) {
         const int l = lh / p.H, h = lh % p.H;
-        const T *kp = bk + l * p.s_bk.layer + h * p.s_bk.head + t * p.s_bk.token + col0;
-        const T *vp = bv + l * p.s_bv.layer + h * p.s_bv.head + t * p.s_bv.token + col0;
-        const u32x4 rklo = load16_stream(kp), rkhi = load16_stream(kp + HALF);
-        const u32x4 rvlo = load16_stream(vp), rvhi = load16_stream(vp + HALF);
+        const T *xp = bp + l * sb.layer + h * sb.head + t * sb.token + col0;
+        const u32x4 rlo = load16_stream(xp), rhi = load16_stream(xp + HALF);
         const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + col0;
         const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN
                                 ? p.weights + ((int64_t)lh * p.S + t) * p.w_pitch
                                 : nullptr;
 
-        float klo[EPV], khi[EPV], vlo[EPV], vhi[EPV];
-        unpack<T>(rklo, klo);
-        unpack<T>(rkhi, khi);
-        unpack<T>(rvlo, vlo);
-        unpack<T>(rvhi, vhi);
-        if (p.base_tab) {
+        float lo[EPV], hi[EPV];
+        unpack<T>(rlo, lo);
+        unpack<T>(rhi, hi);
+        if (rot_base) {
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                const float a = klo[e], b = khi[e];
-                klo[e] = a * bc[e] - b * bs[e];
-                khi[e] = b * bc[e] + a * bs[e];
+                const float a = lo[e], b = hi[e];
+                lo[e] = a * bc[e] - b * bs[e];
+                hi[e] = b * bc[e] + a * bs[e];
             }
         }
 
-        // One anchor: 4 independent 16-byte loads; two anchors are kept in flight.
-        auto accumulate = [&](int a, const u32x4 &rdklo, const u32x4 &rdkhi, const u32x4 &rdvlo, const u32x4 &rdvhi) {
+        auto accumulate = [&](int a, const u32x4 &rdlo, const u32x4 &rdhi) {
             const float w = wrow ? wrow[p.col[a]] : w_lds[row * p.n_sel + a];
-            float dklo[EPV], dkhi[EPV], dvlo[EPV], dvhi[EPV];
-            unpack<T>(rdklo, dklo);
-            unpack<T>(rdkhi, dkhi);
-            unpack<T>(rdvlo, dvlo);
-            unpack<T>(rdvhi, dvhi);
-            const int tb = p.tab[a];
+            float dlo[EPV], dhi[EPV];
+            unpack<T>(rdlo, dlo);
+            unpack<T>(rdhi, dhi);
+            const int tb = is_k ? p.tab[a] : 0;
             if (tb) {
                 const float2 *tcs = cs + (tb - 1) * HALF + lir * EPV;
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) {
                     const float2 v = tcs[e];
-                    const float x = dklo[e], y = dkhi[e];
-                    dklo[e] = x * v.x - y * v.y;
-                    dkhi[e] = y * v.x + x * v.y;
+                    const float x = dlo[e], y = dhi[e];
+                    dlo[e] = x * v.x - y * v.y;
+                    dhi[e] = y * v.x + x * v.y;
                 }
             }
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                klo[e] += w * dklo[e];
-                khi[e] += w * dkhi[e];
-                vlo[e] += w * dvlo[e];
-                vhi[e] += w * dvhi[e];
+                lo[e] += w * dlo[e];
+                hi[e] += w * dhi[e];
             }
         };
 
+        // Four anchors (eight independent 16-byte loads) are kept in flight.
         int a = 0;
-        for (; a + 2 <= p.n_sel; a += 2) {
-            const T *dk0 = static_cast<const T *>(p.dk[a]) + aoff, *dv0 = static_cast<const T *>(p.dv[a]) + aoff;
-            const T *dk1 = static_cast<const T *>(p.dk[a + 1]) + aoff, *dv1 = static_cast<const T *>(p.dv[a + 1]) + aoff;
-            const u32x4 x0 = load16_stream(dk0), x1 = load16_stream(dk0 + HALF);
-            const u32x4 x2 = load16_stream(dv0), x3 = load16_stream(dv0 + HALF);
-            const u32x4 y0 = load16_stream(dk1), y1 = load16_stream(dk1 + HALF);
-            const u32x4 y2 = load16_stream(dv1), y3 = load16_stream(dv1 + HALF);
-            accumulate(a, x0, x1, x2, x3);
-            accumulate(a + 1, y0, y1, y2, y3);
+        for (; a + 4 <= p.n_sel; a += 4) {
+            u32x4 x[4][2];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const T *d = static_cast<const T *>(p.anc[which][a + u]) + aoff;
+                x[u][0] = load16_stream(d);
+                x[u][1] = load16_stream(d + HALF);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
         }
-        if (a < p.n_sel) {
-            const T *dk0 = static_cast<const T *>(p.dk[a]) + aoff, *dv0 = static_cast<const T *>(p.dv[a]) + aoff;
-            const u32x4 x0 = load16_stream(dk0), x1 = load16_stream(dk0 + HALF);
-            const u32x4 x2 = load16_stream(dv0), x3 = load16_stream(dv0 + HALF);
-            accumulate(a, x0, x1, x2, x3);
+        for (; a < p.n_sel; ++a) {
+            const T *d = static_cast<const T *>(p.anc[which][a]) + aoff;
+            const u32x4 x0 = load16_stream(d), x1 = load16_stream(d + HALF);
+            accumulate(a, x0, x1);
         }
 
-        T *okp = ok + l * p.s_ok.layer + h * p.s_ok.head + t * p.s_ok.token + col0;
-        T *ovp = ov + l * p.s_ov.layer + h * p.s_ov.head + t * p.s_ov.token + col0;
-        store16_stream(okp, pack<T>(klo));
-        store16_stream(okp + HALF, pack<T>(khi));
-        store16_stream(ovp, pack<T>(vlo));
-        store16_stream(ovp + HALF, pack<T>(vhi));
+        T *yp = op + l * so.layer + h * so.head + t * so.token + col0;
+        store16_stream(yp, pack<T>(lo));
+        store16_stream(yp + HALF, pack<T>(hi));
     }
 }
 
@@ -186,7 +185,7 @@ int launch_align(const AlignParams &p, int n_blocks, hipStream_t stream)
     constexpr int HALF = LPR * Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
     const size_t lds = sizeof(float2) * (size_t)p.n_tab * HALF + sizeof(float) * (size_t)RPB * p.n_sel;
-    hipLaunchKernelGGL((align_kernel<T, LPR>), dim3(n_blocks), dim3(kBlock), lds, stream, p);
+    hipLaunchKernelGGL((align_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
     return launch_status();
 }
 
@@ -213,14 +212,14 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
     }
 
     AlignParams p{};
-    p.base_k = base_k.ptr;
-    p.base_v = base_v.ptr;
-    p.out_k = out_k.ptr;
-    p.out_v = out_v.ptr;
-    p.s_bk = strides_of(base_k);
-    p.s_bv = strides_of(base_v);
-    p.s_ok = strides_of(out_k);
-    p.s_ov = strides_of(out_v);
+    p.base[0] = base_k.ptr;
+    p.base[1] = base_v.ptr;
+    p.out[0] = out_k.ptr;
+    p.out[1] = out_v.ptr;
+    p.s_base[0] = strides_of(base_k);
+    p.s_base[1] = strides_of(base_v);
+    p.s_out[0] = strides_of(out_k);
+    p.s_out[1] = strides_of(out_v);
     p.s_anc = strides_of(anchor_layout);
     p.weights = weights;
     p.H = model->n_kv_heads;
@@ -228,7 +227,8 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
     p.LH = model->n_layers * model->n_kv_heads;
     p.w_pitch = n_anchors;
     p.gran = gran;
-    p.log2_theta = log2(model->rope_theta);
+    for (int i = 0; i < model->head_dim / 2; ++i)
+        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
 
     // Rotation tables: one per distinct non-zero position delta (base keys: delta_pos;
     // anchor a's deviation: delta_pos - anchor_delta_pos[a]).
@@ -245,8 +245,8 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
         if (anchor_len[a] < seg_len) continue;  // not selected: never read
         if (!anchor_dk[a] || !anchor_dv[a] || !aligned16(anchor_dk[a]) || !aligned16(anchor_dv[a])) return KVCOMM_EINVAL;
         const int s = p.n_sel++;
-        p.dk[s] = anchor_dk[a];
-        p.dv[s] = anchor_dv[a];
+        p.anc[0][s] = anchor_dk[a];
+        p.anc[1][s] = anchor_dv[a];
         p.col[s] = (uint8_t)a;
         p.tab[s] = (uint8_t)(anchor_delta_pos ? table_of(delta_pos - anchor_delta_pos[a]) : 0);
     }
@@ -255,9 +255,9 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
     const int lpr = model->head_dim / (2 * (16 / es));
     const int rpb = kBlock / lpr;
     p.n_token_tiles = (seg_len + rpb - 1) / rpb;
-    // Enough blocks to fill 256 CUs several times over, while each block still walks a few
-    // (layer, head) pairs so that its table / weight set-up is amortised.
-    const int target_blocks = 4096;
+    // Many small blocks: the memory system delivers more with more wavefronts in flight, and the
+    // per-block set-up (weights, cos/sin) is a few dozen instructions.
+    const int target_blocks = 32768;
     int n_chunks = (target_blocks + p.n_token_tiles - 1) / p.n_token_tiles;
     if (n_chunks > p.LH) n_chunks = p.LH;
     if (n_chunks < 1) n_chunks = 1;
