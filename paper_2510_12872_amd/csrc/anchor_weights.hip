@@ -7,7 +7,7 @@
 //   1. dist_partial_kernel streams the key rows once (HBM-bound: (A+1) rows per
 //      (layer, head, token)) and leaves, per block, the squared distance of its chunk of
 //      (layer, head) pairs: partial[chunk][token][anchor] in double.
-//   2. finalize_kernel adds the chunks in index order, takes the square root and the
+//   2. finalize_kernel adds the chunks in a fixed order, takes the square root and the
 //      softmax in double, and writes fp32 weights, the nearest anchor and the selection.
 // Squared differences are accumulated in double so that fp32 inputs keep ~1e-7 relative
 // accuracy in the weights and the arg-min is decided in the precision the definition uses.
@@ -41,7 +41,7 @@ DistPlan make_plan(const kvcomm_model *m, int seg_len, int gran)
     if (gran == KVCOMM_W_LAYER_HEAD_TOKEN) {
         pl.lh_per_block = 1;
     } else {
-        const int target_blocks = 2048;
+        const int target_blocks = 2048;  // measured best on MI355X among 1024 / 2048 / 4096 / 8192
         int n_chunks = (target_blocks + pl.n_token_tiles - 1) / pl.n_token_tiles;
         if (n_chunks > LH) n_chunks = LH;
         if (n_chunks < 1) n_chunks = 1;
@@ -126,7 +126,7 @@ struct FinalParams {
     float *weights;
     int32_t *nearest;
     int32_t *selected_out;
-    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran;
+    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran, chunk_lanes;
     double tau;
     uint8_t col[KVCOMM_MAX_ANCHORS];   // original index of selected anchor
     uint8_t is_sel[KVCOMM_MAX_ANCHORS];
@@ -155,7 +155,9 @@ __device__ __forceinline__ void slot_softmax(const FinalParams &p, const double 
     }
 }
 
-// Per-token and per-(layer, head, token) granularity: thread = (slot, selected anchor).
+// Per-token and per-(layer, head, token) granularity.  A (slot, selected anchor) pair is summed by
+// CL lanes: lane c adds chunks c, c + CL, ... in increasing order and a fixed butterfly joins the
+// lanes, so the result does not depend on timing; the chunk loads of a lane are all in flight at once.
 __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
 {
     __shared__ double dsh[kBlock];
@@ -169,21 +171,23 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
         }
         return;
     }
-    const int spb = kBlock / p.n_sel;  // slots per block
-    const int sl = tid / p.n_sel, a = tid % p.n_sel;
+    const int CL = p.chunk_lanes;          // power of two, CL * n_sel <= kBlock
+    const int spb = kBlock / (CL * p.n_sel);  // slots per block
+    const int cl = tid % CL, a = (tid / CL) % p.n_sel, sl = tid / (CL * p.n_sel);
     const int64_t slot = (int64_t)blockIdx.x * spb + sl;
     const bool active = sl < spb && slot < p.n_slots;
+    double s = 0.0;
     if (active) {
-        double s = 0.0;
         if (p.gran == KVCOMM_W_TOKEN) {
-            for (int c = 0; c < p.n_chunks; ++c) s += p.partial[((int64_t)c * p.S + slot) * p.n_sel + a];
-        } else {
+            for (int c = cl; c < p.n_chunks; c += CL) s += p.partial[((int64_t)c * p.S + slot) * p.n_sel + a];
+        } else if (cl == 0) {
             s = p.partial[slot * p.n_sel + a];  // one chunk per (layer, head): slot = chunk * S + t
         }
-        dsh[sl * p.n_sel + a] = sqrt(s);
     }
+    for (int off = CL / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);  // lanes of a pair are adjacent
+    if (active && cl == 0) dsh[sl * p.n_sel + a] = sqrt(s);
     __syncthreads();
-    if (active) slot_softmax(p, dsh + sl * p.n_sel, a, slot);
+    if (active && cl == 0) slot_softmax(p, dsh + sl * p.n_sel, a, slot);
 }
 
 // Per-segment granularity: one block; each selected anchor's partials are added by the 256
@@ -316,7 +320,11 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
     if (gran == KVCOMM_W_SEGMENT) {
         hipLaunchKernelGGL(finalize_segment_kernel, dim3(1), dim3(kBlock), 0, s, fp);
     } else {
-        const int spb = dp.n_sel > 0 ? kBlock / dp.n_sel : kBlock;
+        int cl = 1;
+        if (gran == KVCOMM_W_TOKEN && dp.n_sel > 0)
+            while (cl < 8 && 2 * cl * dp.n_sel <= kBlock && 2 * cl <= pl.n_chunks) cl *= 2;
+        fp.chunk_lanes = cl;
+        const int spb = dp.n_sel > 0 ? kBlock / (cl * dp.n_sel) : kBlock;
         const int n_blocks = (fp.n_slots + spb - 1) / spb;
         hipLaunchKernelGGL(finalize_kernel, dim3(n_blocks), dim3(kBlock), 0, s, fp);
     }
