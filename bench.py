@@ -25,18 +25,23 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, GB/s
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
+# HBM bytes per launch on this workload (read + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
+# (profiles/bench_llama8b_5agents_hbm_traffic.md).  Not measured live: counters need the profiler.
+HBM_TRAFFIC_BYTES = {"align_kv": 604122828 + 67108866, "anchor_weights": 302106675 + 2097294 + 2180060 + 20512,
+                     "suffix_attn": 537169465 + 134219516}
 
 
 def cpu_baseline(w):
-    """Oracle (as it stands) on a bounded sample: two full segment alignments (all layers) plus the
-    attention of 6 layers of one agent; scaled to the whole workload by segment / layer / agent counts."""
+    """Oracle (as it stands) on a bounded sample: four full segment alignments (all layers) plus the
+    suffix attention of one whole agent; scaled to the whole workload by segment / agent counts."""
     import torch
 
     import oracle
     from paper_2510_12872_amd import workloads
 
     f64 = lambda t: t.to(torch.float64).numpy()
-    n_seg = 2
+    n_seg = 4
     t_align_sample = 0.0
     for j in range(n_seg):
         seg = workloads.make_segment(w, 0, j, "cpu")
@@ -48,7 +53,7 @@ def cpu_baseline(w):
         del seg, args
     t_align = t_align_sample * (w.n_segments * w.n_agents / n_seg)
 
-    sl = 6                                   # layers of one agent, all q heads
+    sl = w.n_layers                          # every layer and q head of one agent
     wa = workloads.scaled(w, n_layers=sl, n_agents=1, n_segments=0, prefix_len=w.n_ctx)
     ag = workloads.make_agent(wa, 0, "cpu")
     q, k, v = f64(ag.q), f64(ag.cache_k), f64(ag.cache_v)
@@ -76,6 +81,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy five times (reference reading for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -90,6 +97,15 @@ def main():
     kv.load_library()  # fails loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4,
+                                               "launches": 5}}))
+        return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
 
@@ -147,18 +163,18 @@ def main():
         ach = seg_w.align_bytes() / (t_align * 1e-3) / 1e9
         kernels["align_kv"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_align,
-                               "bytes_per_launch": seg_w.align_bytes(), "traffic": None}
+                               "bytes_per_launch": seg_w.align_bytes(), "traffic": HBM_TRAFFIC_BYTES["align_kv"]}
     if t_weights:
         ach = seg_w.distance_bytes() / (t_weights * 1e-3) / 1e9
         kernels["anchor_weights"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                      "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_weights,
-                                     "bytes_per_launch": seg_w.distance_bytes(), "traffic": None,
+                                     "bytes_per_launch": seg_w.distance_bytes(), "traffic": HBM_TRAFFIC_BYTES["anchor_weights"],
                                      "note": "two kernels per call (partial distances + softmax finalize)"}
     if t_attn:
         ach = agent_w.attn_flops() / (t_attn * 1e-3) / 1e12
         kernels["suffix_attn"] = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                   "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn,
-                                  "flops_per_launch": agent_w.attn_flops(), "traffic": None}
+                                  "flops_per_launch": agent_w.attn_flops(), "traffic": HBM_TRAFFIC_BYTES["suffix_attn"]}
     # dominant kernel = the one with the largest share of a step
     share = {"align_kv": (t_align or 0) * w.n_agents * w.n_segments,
              "anchor_weights": (t_weights or 0) * w.n_agents * w.n_segments,
