@@ -162,11 +162,11 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // One instruction fills RPL consecutive key rows.  Addresses are a wavefront-uniform row pointer
     // plus a per-lane byte offset that does not change from tile to tile.
     // In a 64-key group, wavefront w fills keys [RW*w, RW*w + RW); load `it` fills rows RW*w + it*RPL ...
-    auto in_row_k = [&](int it) -> int {  // swizzled source chunk (bytes inside the row), K
+    auto in_row_k = [&](int it) __attribute__((always_inline)) -> int {  // swizzled source chunk (bytes inside the row), K
         const int key = wave * RW + it * RPL + lane / KCH;   // only the row index modulo 16 matters
         return ((lane % KCH) ^ (key & KSWZ)) * 16;
     };
-    auto in_row_v = [&](int it) -> int {  // same for V (identical for every `it` when RPL is a multiple of 4)
+    auto in_row_v = [&](int it) __attribute__((always_inline)) -> int {  // same for V (identical for every `it` when RPL is a multiple of 4)
         const int key = wave * RW + it * RPL + lane / KCH;
         return ((lane % KCH) ^ ((4 * (key & 3)) & VSWZ)) * 16;
     };
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // A half outside [0, n_sub) is skipped.  The lower NW/2 wavefronts fill the first half, the rest the second.
     // `clamp` (a literal at every call site) re-reads the last row for rows past the cache end; such
     // rows are never unmasked.  Without it the caller guarantees that all 64 rows exist.
-    auto load_k64 = [&](int key0, bool clamp) {
+    auto load_k64 = [&](int key0, bool clamp) __attribute__((always_inline)) {
         const int h = key0 / 32 + wave / (NW / 2);
         if (h < 0 || h >= n_sub) return;  // wavefront-uniform
         const int rbase = (wave % (NW / 2)) * RW;
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
                                              16, 0, 0);
         }
     };
-    auto load_v64 = [&](int tile, bool clamp) {
+    auto load_v64 = [&](int tile, bool clamp) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 64 * tile + wave * RW + it * RPL;
@@ -233,16 +233,16 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // their shadow: each MFMA is followed by a small chunk of independent VALU instructions and a
     // scheduling barrier pins that order, so the matrix pipe and the vector ALU stay busy together.
     // LDS operands are fetched two MFMAs ahead.
-    auto read_k = [&](const lds_byte *kl, int ks) -> bf16x8 {
+    auto read_k = [&](const lds_byte *kl, int ks) __attribute__((always_inline)) -> bf16x8 {
         return as_bf16x8(*(const __attribute__((address_space(3))) u32x4 *)(kl + k_off[ks]));
     };
-    auto read_v = [&](const lds_byte *vl, int i) -> bf16x8 {  // i = ks * NDB + db
+    auto read_v = [&](const lds_byte *vl, int i) __attribute__((always_inline)) -> bf16x8 {  // i = ks * NDB + db
         const lds_byte *va = vl + (i / NDB) * 16 * ROWB + v_off[i % NDB];
         return lds_read_tr_pair(va, va + 8 * ROWB);
     };
 
     // S^T = K Q^T alone (prologue).
-    auto qk_sub = [&](int u, f32x16 (&s)[QB]) {
+    auto qk_sub = [&](int u, f32x16 (&s)[QB]) __attribute__((always_inline)) {
         const lds_byte *kl = kring + (u & 3) * HALFB;
 #pragma unroll
         for (int b = 0; b < QB; ++b)
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
 
     // Mask and running maximum of S(u) (lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4), in chunks:
     // chunk c of NC folds elements [16c/NC, 16(c+1)/NC) into mx.
-    auto max_chunk = [&](int b, int u, bool masked, f32x16 &s, float &mx, int c, int NC) {
+    auto max_chunk = [&](int b, int u, bool masked, f32x16 &s, float &mx, int c, int NC) __attribute__((always_inline)) {
         const int limit = p.n_ctx + qi[b] - 32 * u;  // last visible key, relative to the sub-step
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // below 2^kLazyLog2 -- harmless in fp32 / bf16 -- and O is rescaled on very few sub-steps.  The
     // result is mathematically the same: numerator and denominator share the reference.
     // Returns the factor by which O has to be rescaled (exactly 1 if the reference stayed).
-    auto max_finish = [&](int b, float mx) -> float {
+    auto max_finish = [&](int b, float mx) __attribute__((always_inline)) -> float {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         // m == -inf only before the first sub-step, where key 0 makes mx finite
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     };
     // Exponentials against the reference maximum, packed bf16 B operands, and the row sum taken from
     // the ROUNDED values (v_dot2_f32_bf16 with ones), so that numerator and denominator agree.
-    auto exp_chunk = [&](f32x16 &s, u32x4 (&pk)[2], float mc, float &rs, int c, int NC) {
+    auto exp_chunk = [&](f32x16 &s, u32x4 (&pk)[2], float mc, float &rs, int c, int NC) __attribute__((always_inline)) {
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             }
         }
     };
-    auto rescale = [&](int b, float corr) {
+    auto rescale = [&](int b, float corr) __attribute__((always_inline)) {
         // only when the reference of some query of the wavefront moved (rare after the first tiles)
         if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
 #pragma unroll
@@ -316,7 +316,9 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     //   B: O += V(u) P(u) on the matrix cores        ||  mask + running max of S(u+1)
     //   C: rescale O if that maximum moved (after B, before the next sub-step is added).
     // With has_next == false only the exponentials and the second product run.
-    auto substep = [&](int u, bool has_next, bool next_masked, f32x16 (&s_a)[QB], f32x16 (&s_b)[QB]) {
+    // `u4` must equal u & 3 and is a literal at every call site: it fixes the K ring slot and the V
+    // buffer, so every LDS operand address is a per-lane register plus an immediate offset.
+    auto substep = [&](int u, int u4, bool has_next, bool next_masked, f32x16 (&s_a)[QB], f32x16 (&s_b)[QB]) __attribute__((always_inline)) {
         u32x4 pk[QB][2];
         float mc[QB], rs[QB];
 #pragma unroll
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             rs[b] = 0.f;
         }
         if (has_next) {
-            const lds_byte *kl = kring + ((u + 1) & 3) * HALFB;
+            const lds_byte *kl = kring + ((u4 + 1) & 3) * HALFB;
             bf16x8 ka[NKS];
             ka[0] = read_k(kl, 0);
             ka[1] = read_k(kl, 1);
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             pf[b][1] = as_bf16x8(pk[b][1]);
         }
 
-        const lds_byte *vl = vbuf + ((u >> 1) & 1) * TILEB + (u & 1) * HALFB;
+        const lds_byte *vl = vbuf + ((u4 >> 1) & 1) * TILEB + (u4 & 1) * HALFB;
         constexpr int NPV = 2 * NDB;
         bf16x8 va[NPV];
         va[0] = read_v(vl, 0);
@@ -381,7 +383,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         }
 
     };
-    const auto tile_barrier = [&]() {
+    const auto tile_barrier = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed in LDS
         __syncthreads();                     // ... and everybody else's; what was read in this tile is free
     };
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     const int t_last = n_tiles - 1;
     // Leading tiles that need no mask in either sub-step (nor in the first sub-step of the next
     // tile, whose maximum is taken at their end) and whose look-ahead loads stay inside the cache.
-    const int t_safe = p.N >= 160 ? (p.N - 160) / 64 + 1 : 0;  // tile t loads keys up to 64t + 159
+    const int t_safe = p.N >= 224 ? (p.N - 224) / 64 + 1 : 0;  // a tile pair starting at t loads keys up to 64t + 223
     const int t_plain = max(0, min(min((sub_unmasked - 1) >> 1, t_last), t_safe));
 #pragma unroll
     for (int b = 0; b < QB; ++b) {  // maximum of sub-step 0; O is still zero, so there is nothing to rescale
@@ -408,23 +410,35 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         for (int c = 0; c < 4; ++c) max_chunk(b, 0, true, s0[b], mx, c, 4);
         (void)max_finish(b, mx);
     }
-    int t = 0;
-    for (; t < t_plain; ++t) {
-        load_k64(64 * t + 96, false);
-        load_v64(t + 1, false);
-        substep(2 * t, true, false, s0, s1);
-        substep(2 * t + 1, true, false, s1, s0);
+    // Two tiles (four sub-steps) per trip so that ring slots and buffers are compile-time constants.
+    auto tile_pair = [&](int t, bool clamp, bool masked) __attribute__((always_inline)) {
+        load_k64(64 * t + 96, clamp);
+        load_v64(t + 1, clamp);
+        substep(2 * t, 0, true, masked, s0, s1);
+        substep(2 * t + 1, 1, true, masked, s1, s0);
         tile_barrier();
-    }
-    for (; t < t_last; ++t) {
+        load_k64(64 * t + 160, clamp);
+        load_v64(t + 2, clamp);
+        substep(2 * t + 2, 2, true, masked, s0, s1);
+        substep(2 * t + 3, 3, true, masked, s1, s0);
+        tile_barrier();
+    };
+    int t = 0;
+    for (; t + 2 <= t_plain; t += 2) tile_pair(t, false, false);
+    for (; t + 2 <= t_last; t += 2) tile_pair(t, true, true);
+    if (t < t_last) {  // one more tile with a successor (t is even)
         load_k64(64 * t + 96, true);
         load_v64(t + 1, true);
-        substep(2 * t, true, true, s0, s1);
-        substep(2 * t + 1, true, true, s1, s0);
+        substep(2 * t, 0, true, true, s0, s1);
+        substep(2 * t + 1, 1, true, true, s1, s0);
         tile_barrier();
+        ++t;
+        substep(2 * t, 2, true, true, s0, s1);
+        substep(2 * t + 1, 3, false, false, s1, s0);  // the last sub-step has no successor
+    } else {
+        substep(2 * t, 0, true, true, s0, s1);
+        substep(2 * t + 1, 1, false, false, s1, s0);
     }
-    substep(2 * t, true, true, s0, s1);
-    substep(2 * t + 1, false, false, s1, s0);  // the last sub-step has no successor
 
     // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
 #pragma unroll
