@@ -58,6 +58,16 @@ def _load():
         lib.kvo_align.restype = None
         lib.kvo_suffix_attn.argtypes = [dp, dp, dp] + [ctypes.c_int] * 6 + [ctypes.c_double, dp, dp]
         lib.kvo_suffix_attn.restype = None
+        lib.kvo_capture.argtypes = [dp, dp, dp, dp] + [ctypes.c_int] * 4 + [ctypes.c_double, ctypes.c_double, dp, dp]
+        lib.kvo_capture.restype = None
+        lib.kvo_predict.argtypes = [dp, ip, ip, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, ctypes.c_double, dp, dp]
+        lib.kvo_predict.restype = ctypes.c_int
+        lib.kvo_cosine.argtypes = [dp, dpp, ip] + [ctypes.c_int] * 6 + [dp, ip]
+        lib.kvo_cosine.restype = None
+        lib.kvo_weights_from_sim.argtypes = [dp, ip, ctypes.c_int, ctypes.c_size_t, ctypes.c_double, dp, ip]
+        lib.kvo_weights_from_sim.restype = None
+        lib.kvo_weights_nearest.argtypes = [dp, ip, ctypes.c_int, ctypes.c_size_t, dp, ip]
+        lib.kvo_weights_nearest.restype = None
         lib.kvo_num_threads.argtypes = []
         lib.kvo_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -179,3 +189,63 @@ def reuse_step(seg_k, seg_v, anc_k, anc_dk, anc_dv, delta, theta, tau=1.0, anc_d
     w, nearest = weights(dist, selected, tau)
     out_k, out_v = align(seg_k, seg_v, anc_dk, anc_dv, w, delta, theta, anc_delta, gran)
     return dict(dist=dist, selected=selected, w=w, nearest=nearest, out_k=out_k, out_v=out_v)
+
+
+def capture(base_k, base_v, real_k, real_v, delta, theta):
+    """Offset capture: (dK, dV) such that align with this single anchor and weight 1 returns the real cache."""
+    base_k, base_v, real_k, real_v = _f64(base_k), _f64(base_v), _f64(real_k), _f64(real_v)
+    L, H, S, D = base_k.shape
+    assert base_v.shape == real_k.shape == real_v.shape == base_k.shape
+    dk, dv = np.empty_like(base_k), np.empty_like(base_k)
+    _load().kvo_capture(_dptr(base_k), _dptr(base_v), _dptr(real_k), _dptr(real_v), L, H, S, D,
+                        float(delta), float(theta), _dptr(dk), _dptr(dv))
+    return dk, dv
+
+
+def predict(w, selected, anc_len, seg_len, gamma):
+    """Anchor prediction of Eq. "pred".  w [A,n].  Returns (new_anchor 0/1, entropy [n], mean entropy)."""
+    w = _f64(w)
+    A, n = w.shape
+    selected = np.ascontiguousarray(np.asarray(selected, dtype=np.intc))
+    anc_len = np.ascontiguousarray(np.asarray(anc_len, dtype=np.intc))
+    ent = np.zeros(n, dtype=np.float64)
+    mean = ctypes.c_double(0.0)
+    r = _load().kvo_predict(_dptr(w), _iptr(selected), _iptr(anc_len), A, n, int(seg_len), float(gamma),
+                            _dptr(ent), ctypes.byref(mean))
+    return int(r), ent, mean.value
+
+
+def cosine(seg_k, anc_k, gran=GRAN_TOKEN):
+    """Cosine similarity of base keys per weight slot.  Returns (sim [A,n], selected [A])."""
+    seg_k = _f64(seg_k)
+    L, H, S, D = seg_k.shape
+    anc = [_f64(a) for a in anc_k]
+    A = len(anc)
+    anc_len = np.array([a.shape[2] for a in anc], dtype=np.intc)
+    n = gran_count(gran, L, H, S)
+    sim = np.zeros((A, n), dtype=np.float64)
+    selected = np.zeros(A, dtype=np.intc)
+    _load().kvo_cosine(_dptr(seg_k), _ptr_array(anc), _iptr(anc_len), A, L, H, S, D, gran, _dptr(sim), _iptr(selected))
+    return sim, selected
+
+
+def weights_from_sim(sim, selected, tau=1.0):
+    """softmax(sim / tau) over selected anchors.  Returns (w [A,n], best [n])."""
+    sim = _f64(sim)
+    A, n = sim.shape
+    selected = np.ascontiguousarray(np.asarray(selected, dtype=np.intc))
+    w = np.zeros((A, n), dtype=np.float64)
+    best = np.zeros(n, dtype=np.intc)
+    _load().kvo_weights_from_sim(_dptr(sim), _iptr(selected), A, n, float(tau), _dptr(w), _iptr(best))
+    return w, best
+
+
+def weights_nearest(dist, selected):
+    """One-hot weights at the selected anchor of smallest distance.  Returns (w [A,n], nearest [n])."""
+    dist = _f64(dist)
+    A, n = dist.shape
+    selected = np.ascontiguousarray(np.asarray(selected, dtype=np.intc))
+    w = np.zeros((A, n), dtype=np.float64)
+    nearest = np.zeros(n, dtype=np.intc)
+    _load().kvo_weights_nearest(_dptr(dist), _iptr(selected), A, n, _dptr(w), _iptr(nearest))
+    return w, nearest

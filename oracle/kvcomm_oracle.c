@@ -262,3 +262,144 @@ int kvo_num_threads(void) { return omp_get_max_threads(); }
 #else
 int kvo_num_threads(void) { return 1; }
 #endif
+
+/* ------------------------------------------------------------------------- */
+/* O6.  Offset capture (fallback branch of Algorithm 1: after a dense generation the
+ * offset between the real and the base KV-cache of a placeholder, and of its
+ * neighbouring prefix segment, fills a new anchor).  The deviation is stored in
+ * the frame of the position delta it was recorded at, i.e. the inverse of O4
+ * with a single anchor of weight 1:
+ *   dK[l,h,t,:] = K_real[l,h,t,:] - R_delta K_base[l,h,t,:]
+ *   dV[l,h,t,:] = V_real[l,h,t,:] -         V_base[l,h,t,:]                   */
+void kvo_capture(const double *base_k, const double *base_v, const double *real_k, const double *real_v,
+                 int L, int H, int S, int D, double delta, double theta, double *dk, double *dv)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int l = 0; l < L; ++l)
+        for (int h = 0; h < H; ++h) {
+            double *rot = (double *)malloc(sizeof(double) * (size_t)D);
+            for (int t = 0; t < S; ++t) {
+                size_t row = (((size_t)l * H + h) * S + t) * D;
+                kvo_rope_rotate(base_k + row, rot, D, delta, theta);
+                for (int i = 0; i < D; ++i) {
+                    dk[row + i] = real_k[row + i] - rot[i];
+                    dv[row + i] = real_v[row + i] - base_v[row + i];
+                }
+            }
+            free(rot);
+        }
+}
+
+/* ------------------------------------------------------------------------- */
+/* O7.  Anchor prediction (Eq. "pred"): a sample becomes a new anchor when it is
+ * longer than every anchor of the pool, or when the entropy of its weights over
+ * the candidate anchors exceeds gamma * log |A_phi|.  The printed entropy lacks
+ * its minus sign (it would be <= 0 and never exceed a non-negative threshold);
+ * the sensitivity table (reuse rising with gamma) fixes H = - sum w log w.
+ *   entropy[j] = - sum_{a selected, w > 0} w[a,j] log w[a,j]      per weight slot
+ * The decision compares the mean entropy over the n slots (n = 1 for per-segment
+ * weights, which is the paper's scalar case).  Returns 1 = new anchor, 0 = shareable.
+ * An empty candidate set (no anchor as long as the sample) is case one.       */
+int kvo_predict(const double *w, const int *selected, const int *anc_len, int A, size_t n,
+                int seg_len, double gamma, double *entropy, double *mean_entropy)
+{
+    int n_sel = 0, max_len = 0;
+    for (int a = 0; a < A; ++a) {
+        if (selected[a]) ++n_sel;
+        if (anc_len[a] > max_len) max_len = anc_len[a];
+    }
+    double sum = 0.0;
+    for (size_t j = 0; j < n; ++j) {
+        double hj = 0.0;
+        for (int a = 0; a < A; ++a) {
+            double x = w[(size_t)a * n + j];
+            if (selected[a] && x > 0.0) hj -= x * log(x);
+        }
+        entropy[j] = hj;
+        sum += hj;
+    }
+    *mean_entropy = n ? sum / (double)n : 0.0;
+    if (seg_len > max_len) return 1;
+    if (n_sel == 0) return 1;
+    return (*mean_entropy > gamma * log((double)n_sel)) ? 1 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* O8.  Weighting variants of the approximation-method ablation (appendix "Analysis
+ * on the Approximation Method"):
+ *   nearest: the whole weight goes to the selected anchor of smallest l2 distance
+ *            (lowest index among equals);
+ *   cosine : softmax across anchors of the cosine similarity between the segment's
+ *            and the anchor's base keys, reduced over the same axes as the distance.
+ * kvo_cosine writes sim[a, j] = <x, y> / (|x| |y|) for selected anchors (0 when a
+ * norm is 0) and 0 for the others; kvo_weights_from_sim turns similarities into
+ * softmax(sim / tau) over selected anchors; kvo_weights_nearest builds the one-hot. */
+void kvo_cosine(const double *seg_k, const double *const *anc_k, const int *anc_len,
+                int A, int L, int H, int S, int D, int gran, double *sim, int *selected)
+{
+    size_t n = gran_count(gran, L, H, S);
+    double *dot = (double *)malloc(sizeof(double) * n);
+    double *nx = (double *)malloc(sizeof(double) * n);
+    double *ny = (double *)malloc(sizeof(double) * n);
+    for (int a = 0; a < A; ++a) {
+        selected[a] = (anc_len[a] >= S) ? 1 : 0;
+        for (size_t j = 0; j < n; ++j) sim[(size_t)a * n + j] = 0.0;
+        if (!selected[a]) continue;
+        for (size_t j = 0; j < n; ++j) dot[j] = nx[j] = ny[j] = 0.0;
+        int Sa = anc_len[a];
+        for (int l = 0; l < L; ++l)
+            for (int h = 0; h < H; ++h)
+                for (int t = 0; t < S; ++t) {
+                    size_t j = gran_index(gran, H, S, l, h, t);
+                    for (int i = 0; i < D; ++i) {
+                        double u = seg_k[(((size_t)l * H + h) * S + t) * D + i];
+                        double v = anc_k[a][(((size_t)l * H + h) * Sa + t) * D + i];
+                        dot[j] += u * v;
+                        nx[j] += u * u;
+                        ny[j] += v * v;
+                    }
+                }
+        for (size_t j = 0; j < n; ++j) {
+            double den = sqrt(nx[j]) * sqrt(ny[j]);
+            sim[(size_t)a * n + j] = den > 0.0 ? dot[j] / den : 0.0;
+        }
+    }
+    free(dot);
+    free(nx);
+    free(ny);
+}
+
+void kvo_weights_from_sim(const double *sim, const int *selected, int A, size_t n, double tau,
+                          double *w, int *best_out)
+{
+    for (size_t j = 0; j < n; ++j) {
+        int best = -1;
+        double smax = 0.0;
+        for (int a = 0; a < A; ++a) {
+            if (!selected[a]) continue;
+            double x = sim[(size_t)a * n + j];
+            if (best < 0 || x > smax) { best = a; smax = x; }
+        }
+        best_out[j] = best;
+        double denom = 0.0;
+        for (int a = 0; a < A; ++a)
+            if (selected[a]) denom += exp((sim[(size_t)a * n + j] - smax) / tau);
+        for (int a = 0; a < A; ++a)
+            w[(size_t)a * n + j] = selected[a] ? exp((sim[(size_t)a * n + j] - smax) / tau) / denom : 0.0;
+    }
+}
+
+void kvo_weights_nearest(const double *dist, const int *selected, int A, size_t n, double *w, int *nearest)
+{
+    for (size_t j = 0; j < n; ++j) {
+        int best = -1;
+        double dmin = 0.0;
+        for (int a = 0; a < A; ++a) {
+            if (!selected[a]) continue;
+            double d = dist[(size_t)a * n + j];
+            if (best < 0 || d < dmin) { best = a; dmin = d; }
+        }
+        nearest[j] = best;
+        for (int a = 0; a < A; ++a) w[(size_t)a * n + j] = (a == best) ? 1.0 : 0.0;
+    }
+}
