@@ -172,6 +172,66 @@ int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q,
                        kvcomm_tensor out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* --------------------------------------------------------------------------------------
+ * Weighting variants of the appendix on the approximation method: the default rule
+ * (softmax of the negative l2 distance), "nearest" (all weight on the selected anchor of
+ * smallest l2 distance) and "cosine" (softmax across anchors of the cosine similarity of
+ * the base keys, reduced over the same axes as the distance).
+ * Same arguments, outputs and errors as kvcomm_anchor_weights, plus `rule`; for
+ * KVCOMM_RULE_COSINE nearest_out holds the anchor of LARGEST similarity.  The workspace
+ * must hold kvcomm_anchor_weights_rule_workspace() bytes for the same rule.              */
+typedef enum {
+    KVCOMM_RULE_L2_SOFTMAX = 0,
+    KVCOMM_RULE_NEAREST = 1,
+    KVCOMM_RULE_COSINE_SOFTMAX = 2
+} kvcomm_rule;
+
+size_t kvcomm_anchor_weights_rule_workspace(const kvcomm_model *model, int32_t seg_len,
+                                            int32_t n_anchors, int32_t gran, int32_t rule);
+
+int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,
+                               kvcomm_tensor seg_base_k, int32_t seg_len,
+                               const void *const *anchor_base_k, kvcomm_tensor anchor_layout,
+                               const int32_t *anchor_len, int32_t n_anchors,
+                               float *weights_out, int32_t *nearest_out, int32_t *selected_out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------------------
+ * Anchor prediction (Eq. "pred"): should a sample become a new anchor?  Yes (1) when it is
+ * longer than every anchor of the pool, when no anchor is at least as long, or when the
+ * entropy of its weights over the candidate anchors, H = -sum_a w log w (the printed formula
+ * lacks the minus sign), exceeds gamma * log(number of candidates).  With more than one
+ * weight slot the mean entropy over the slots is compared.
+ *
+ *   weights        DEVICE [n_slots, n_anchors] fp32 from kvcomm_anchor_weights*.
+ *   anchor_len     HOST [n_anchors]; candidates are the anchors with anchor_len >= seg_len.
+ *   entropy_out    DEVICE [n_slots] fp32 or NULL.
+ *   result_out     DEVICE float[2]: [0] = decision (1.0 new anchor / 0.0 shareable),
+ *                  [1] = mean entropy.
+ *   workspace      DEVICE scratch of kvcomm_anchor_predict_workspace(n_slots) bytes, 8-byte aligned.
+ * Two small kernels; sums are taken in double in a fixed order.
+ * Errors: KVCOMM_EINVAL for null pointers, n_slots <= 0, n_anchors <= 0, seg_len <= 0,
+ * negative anchor_len, gamma < 0 or NaN; KVCOMM_EWORKSPACE.                              */
+size_t kvcomm_anchor_predict_workspace(int64_t n_slots);
+
+int kvcomm_anchor_predict(const float *weights, int64_t n_slots, const int32_t *anchor_len,
+                          int32_t n_anchors, int32_t seg_len, float gamma,
+                          float *entropy_out, float *result_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------------------
+ * Offset capture (fallback branch of Algorithm 1: after a dense generation, the offset
+ * between the real and the base KV-cache fills a new anchor).  Inverse of kvcomm_align_kv
+ * for a single anchor of weight 1 recorded at delta_pos:
+ *   out_dk[l,h,t,:] = real_k[l,h,t,:] - R(delta_pos) base_k[l,h,t,:]
+ *   out_dv[l,h,t,:] = real_v[l,h,t,:] -              base_v[l,h,t,:]
+ * All six tensors are [L, Hkv, seg_len, D]; real_k / real_v are normally views into the
+ * agent's cache at the segment's token offset.  fp32 arithmetic, one rounding at the store.
+ * Errors as for kvcomm_align_kv.                                                         */
+int kvcomm_capture_offsets(const kvcomm_model *model, kvcomm_tensor base_k, kvcomm_tensor base_v,
+                           kvcomm_tensor real_k, kvcomm_tensor real_v, int32_t seg_len, int32_t delta_pos,
+                           kvcomm_tensor out_dk, kvcomm_tensor out_dv, void *stream);
+
 /* Human-readable name of a kvcomm_status; never NULL. */
 const char *kvcomm_status_string(int status);
 

@@ -18,6 +18,9 @@ W_TOKEN = 0
 W_LAYER_HEAD_TOKEN = 1
 W_SEGMENT = 2
 MAX_ANCHORS = 64
+RULE_L2_SOFTMAX = 0
+RULE_NEAREST = 1
+RULE_COSINE_SOFTMAX = 2
 
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 
@@ -88,6 +91,18 @@ def load_library():
     lib.kvcomm_suffix_attn_workspace.restype = sz
     lib.kvcomm_suffix_attn.argtypes = [mp, _CTensor, _CTensor, _CTensor, i32, i32, f32, _CTensor, vp, vp, sz, vp]
     lib.kvcomm_suffix_attn.restype = ctypes.c_int
+    lib.kvcomm_anchor_weights_rule_workspace.argtypes = [mp, i32, i32, i32, i32]
+    lib.kvcomm_anchor_weights_rule_workspace.restype = sz
+    lib.kvcomm_anchor_weights_rule.argtypes = [mp, i32, i32, f32, _CTensor, i32, ctypes.POINTER(vp), _CTensor,
+                                               ctypes.POINTER(i32), i32, vp, vp, vp, vp, sz, vp]
+    lib.kvcomm_anchor_weights_rule.restype = ctypes.c_int
+    lib.kvcomm_anchor_predict_workspace.argtypes = [ctypes.c_int64]
+    lib.kvcomm_anchor_predict_workspace.restype = sz
+    lib.kvcomm_anchor_predict.argtypes = [vp, ctypes.c_int64, ctypes.POINTER(i32), i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.kvcomm_anchor_predict.restype = ctypes.c_int
+    lib.kvcomm_capture_offsets.argtypes = [mp, _CTensor, _CTensor, _CTensor, _CTensor, i32, i32, _CTensor, _CTensor,
+                                           vp]
+    lib.kvcomm_capture_offsets.restype = ctypes.c_int
     lib.kvcomm_status_string.argtypes = [ctypes.c_int]
     lib.kvcomm_status_string.restype = ctypes.c_char_p
     lib.kvcomm_version.argtypes = []
@@ -212,3 +227,81 @@ def kvcomm_suffix_attn(model, q, cache_k, cache_v, n_ctx, softmax_scale=0.0, out
                                   int(n_ctx), tq, float(softmax_scale), _desc(out, model.dtype, "out"),
                                   None if lse_out is None else lse_out.data_ptr(), None, 0, _stream_ptr(stream)))
     return (out, lse_out) if want_lse else out
+
+
+def kvcomm_anchor_weights_rule_workspace(model, seg_len, n_anchors, gran=W_TOKEN, rule=RULE_L2_SOFTMAX):
+    return int(load_library().kvcomm_anchor_weights_rule_workspace(ctypes.byref(model.c()), seg_len, n_anchors, gran,
+                                                                   rule))
+
+
+def kvcomm_anchor_weights_rule(model, rule, seg_base_k, anchor_base_k, anchor_len=None, temperature=1.0, gran=W_TOKEN,
+                               weights_out=None, nearest_out=None, selected_out=None, workspace=None, stream=None):
+    """Anchor matching under one of the weighting variants.  Returns (weights, nearest, selected)."""
+    lib = load_library()
+    seg_len = seg_base_k.shape[2]
+    A = len(anchor_base_k)
+    dev = seg_base_k.device
+    n = kvcomm_weight_slots(model, seg_len, gran)
+    if weights_out is None:
+        weights_out = torch.empty((n, A), dtype=torch.float32, device=dev)
+    if nearest_out is None:
+        nearest_out = torch.empty((n,), dtype=torch.int32, device=dev)
+    if selected_out is None:
+        selected_out = torch.empty((A,), dtype=torch.int32, device=dev)
+    if workspace is None:
+        need = kvcomm_anchor_weights_rule_workspace(model, seg_len, A, gran, rule)
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=dev)
+    ptrs, layout, lens = _anchor_args(anchor_base_k, anchor_len, model.dtype, "anchor_base_k")
+    _check(lib.kvcomm_anchor_weights_rule(ctypes.byref(model.c()), gran, int(rule), float(temperature),
+                                          _desc(seg_base_k, model.dtype, "seg_base_k"), seg_len, ptrs, layout, lens,
+                                          A, weights_out.data_ptr(), nearest_out.data_ptr(), selected_out.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream_ptr(stream)))
+    return weights_out, nearest_out, selected_out
+
+
+def kvcomm_anchor_predict_workspace(n_slots):
+    return int(load_library().kvcomm_anchor_predict_workspace(int(n_slots)))
+
+
+def kvcomm_anchor_predict(weights, anchor_len, seg_len, gamma, entropy_out=None, result_out=None, workspace=None,
+                          want_entropy=False, stream=None):
+    """Eq. "pred" on the device.  weights [n, A] fp32.  Returns result [2] (decision, mean entropy)
+    and, with want_entropy, the per-slot entropies [n]."""
+    lib = load_library()
+    if weights.dim() != 2 or weights.dtype != torch.float32 or not weights.is_contiguous() or not weights.is_cuda:
+        raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
+    n, A = weights.shape
+    if len(anchor_len) != A:
+        raise KVCommError(-1, "anchor_len must have one entry per anchor")
+    dev = weights.device
+    if want_entropy and entropy_out is None:
+        entropy_out = torch.empty((n,), dtype=torch.float32, device=dev)
+    if result_out is None:
+        result_out = torch.empty((2,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty((max(kvcomm_anchor_predict_workspace(n), 8),), dtype=torch.uint8, device=dev)
+    lens = (ctypes.c_int32 * max(A, 1))(*[int(x) for x in anchor_len])
+    _check(lib.kvcomm_anchor_predict(weights.data_ptr(), n, lens, A, int(seg_len), float(gamma),
+                                     None if entropy_out is None else entropy_out.data_ptr(), result_out.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream_ptr(stream)))
+    return (result_out, entropy_out) if want_entropy else result_out
+
+
+def kvcomm_capture_offsets(model, base_k, base_v, real_k, real_v, delta_pos, out_dk=None, out_dv=None, stream=None):
+    """Offset capture: (real - re-positioned base) for keys and values of one segment."""
+    lib = load_library()
+    seg_len = base_k.shape[2]
+    for t in (base_v, real_k, real_v):
+        if t.shape != base_k.shape:
+            raise KVCommError(-1, "base and real tensors must have one shape")
+    if out_dk is None:
+        out_dk = torch.empty(base_k.shape, dtype=model.dtype, device=base_k.device)
+    if out_dv is None:
+        out_dv = torch.empty(base_k.shape, dtype=model.dtype, device=base_k.device)
+    d = lambda t, what: _desc(t, model.dtype, what)
+    _check(lib.kvcomm_capture_offsets(ctypes.byref(model.c()), d(base_k, "base_k"), d(base_v, "base_v"),
+                                      d(real_k, "real_k"), d(real_v, "real_v"), seg_len, int(delta_pos),
+                                      d(out_dk, "out_dk"), d(out_dv, "out_dv"), _stream_ptr(stream)))
+    return out_dk, out_dv

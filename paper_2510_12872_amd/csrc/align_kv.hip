@@ -75,12 +75,7 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
         // cos/sin of delta * theta^(-2i/D): product and reduction modulo 2*pi in double.
         for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock) {
             const int r = idx / HALF, i = idx % HALF;
-            const double x = (double)p.tab_delta[r] * p.inv_freq[i];
-            const double k = rint(x * 0.15915494309189535);               // 1 / (2 pi)
-            double red = fma(-k, 6.283185307179586, x);                   // 2 pi, high part
-            red = fma(-k, 2.4492935982947064e-16, red);                   // 2 pi, low part
-            const float rf = (float)red;
-            cs[idx] = make_float2(cosf(rf), sinf(rf));
+            cs[idx] = rope_cos_sin(p.tab_delta[r], p.inv_freq[i]);
         }
     }
     if (p.gran != KVCOMM_W_LAYER_HEAD_TOKEN) {

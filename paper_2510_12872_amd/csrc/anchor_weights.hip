@@ -11,6 +11,11 @@
 //      softmax in double, and writes fp32 weights, the nearest anchor and the selection.
 // Squared differences are accumulated in double so that fp32 inputs keep ~1e-7 relative
 // accuracy in the weights and the arg-min is decided in the precision the definition uses.
+//
+// kvcomm_anchor_weights_rule adds the two weighting variants of the appendix on the
+// approximation method: "nearest" (same distances, one-hot at the arg-min) and "cosine"
+// (cos_partial_kernel leaves <x,y>, |x|^2 and |y|^2 per chunk; the softmax runs over the
+// similarities).  Both reuse the two-stage structure and the finalize kernels.
 #include <math.h>
 
 #include "kvcomm_device.h"
@@ -121,32 +126,119 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
     }
 }
 
+constexpr int kCosTile = 8;  // anchors per lane in the cosine variant (two accumulators each)
+
+// Cosine variant: per chunk, token and selected anchor the three sums <x,y>, |x|^2, |y|^2
+// (x = segment key row, y = anchor key row), laid out [component][chunk][token][anchor].
+template <typename T, int LPR>
+__global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p, const int64_t comp_stride)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr int RPB = kBlock / LPR;
+    const int tid = threadIdx.x;
+    const int row = tid / LPR, lir = tid % LPR;
+    const int tile = blockIdx.x % p.n_token_tiles;
+    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int a0 = blockIdx.y * kCosTile;
+    const int na = min(kCosTile, p.n_sel - a0);
+    const int t = tile * RPB + row;
+    const bool valid = t < p.S;
+    const int lh0 = chunk * p.lh_per_block;
+    const int lh1 = min(lh0 + p.lh_per_block, p.LH);
+
+    double dot[kCosTile], ny[kCosTile], nx = 0.0;
+#pragma unroll
+    for (int j = 0; j < kCosTile; ++j) dot[j] = ny[j] = 0.0;
+
+    if (valid) {
+        const T *seg = static_cast<const T *>(p.seg_k);
+        for (int lh = lh0; lh < lh1; ++lh) {
+            const int l = lh / p.H, h = lh % p.H;
+            const u32x4 rs = load16_stream(seg + l * p.s_seg.layer + h * p.s_seg.head + t * p.s_seg.token + lir * EPV);
+            const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + lir * EPV;
+            u32x4 ra[kCosTile];
+#pragma unroll
+            for (int j = 0; j < kCosTile; ++j)
+                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[a0 + j]) + aoff);
+            float x[EPV];
+            unpack<T>(rs, x);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) nx = fma((double)x[e], (double)x[e], nx);
+#pragma unroll
+            for (int j = 0; j < kCosTile; ++j)
+                if (j < na) {
+                    float y[EPV];
+                    unpack<T>(ra[j], y);
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) {
+                        dot[j] = fma((double)x[e], (double)y[e], dot[j]);
+                        ny[j] = fma((double)y[e], (double)y[e], ny[j]);
+                    }
+                }
+        }
+    }
+#pragma unroll
+    for (int off = LPR / 2; off >= 1; off >>= 1) nx += __shfl_xor(nx, off, LPR);
+#pragma unroll
+    for (int j = 0; j < kCosTile; ++j) {
+        if (j < na) {
+            double u = dot[j], v = ny[j];
+#pragma unroll
+            for (int off = LPR / 2; off >= 1; off >>= 1) {
+                u += __shfl_xor(u, off, LPR);
+                v += __shfl_xor(v, off, LPR);
+            }
+            if (valid && lir == 0) {
+                const int64_t i = ((int64_t)chunk * p.S + t) * p.n_sel + a0 + j;
+                p.partial[i] = u;
+                p.partial[comp_stride + i] = nx;
+                p.partial[2 * comp_stride + i] = v;
+            }
+        }
+    }
+}
+
 struct FinalParams {
     const double *partial;
     float *weights;
     int32_t *nearest;
     int32_t *selected_out;
-    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran, chunk_lanes;
+    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran, chunk_lanes, rule;
+    int64_t comp_stride;  // cosine rule: elements between the three partial components
     double tau;
     uint8_t col[KVCOMM_MAX_ANCHORS];   // original index of selected anchor
     uint8_t is_sel[KVCOMM_MAX_ANCHORS];
 };
 
-// Softmax over the selected anchors of one slot, evaluated identically by each of the
-// slot's threads from the distances in `d` (LDS): every thread walks the anchors in index
-// order, so all agree bit for bit on the minimum, the arg-min and the denominator.
-__device__ __forceinline__ void slot_softmax(const FinalParams &p, const double *d, int a, int64_t slot)
+// Score whose softmax across anchors gives the weights: minus the l2 distance, or the cosine
+// similarity <x,y> / (|x| |y|) (0 when a norm is 0).
+__device__ __forceinline__ double score_of(const FinalParams &p, double s0, double s1, double s2)
 {
-    double dmin = d[0];
+    if (p.rule != KVCOMM_RULE_COSINE_SOFTMAX) return -sqrt(s0);
+    const double den = sqrt(s1) * sqrt(s2);
+    return den > 0.0 ? s0 / den : 0.0;
+}
+
+// Softmax over the selected anchors of one slot, evaluated identically by each of the
+// slot's threads from the scores in `sc` (LDS): every thread walks the anchors in index
+// order, so all agree bit for bit on the maximum, the arg-max and the denominator.
+__device__ __forceinline__ void slot_softmax(const FinalParams &p, const double *sc, int a, int64_t slot)
+{
+    double smax = sc[0];
     int best = 0;
     for (int j = 1; j < p.n_sel; ++j)
-        if (d[j] < dmin) {
-            dmin = d[j];
+        if (sc[j] > smax) {
+            smax = sc[j];
             best = j;
         }
-    double denom = 0.0;
-    for (int j = 0; j < p.n_sel; ++j) denom += exp(-(d[j] - dmin) / p.tau);
-    const double w = exp(-(d[a] - dmin) / p.tau) / denom;
+    double w;
+    if (p.rule == KVCOMM_RULE_NEAREST) {
+        w = a == best ? 1.0 : 0.0;
+    } else {
+        double denom = 0.0;
+        for (int j = 0; j < p.n_sel; ++j) denom += exp((sc[j] - smax) / p.tau);
+        w = exp((sc[a] - smax) / p.tau) / denom;
+    }
     p.weights[slot * p.n_anchors + p.col[a]] = (float)w;
     if (a == 0) {
         if (p.nearest) p.nearest[slot] = p.col[best];
@@ -176,16 +268,35 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
     const int cl = tid % CL, a = (tid / CL) % p.n_sel, sl = tid / (CL * p.n_sel);
     const int64_t slot = (int64_t)blockIdx.x * spb + sl;
     const bool active = sl < spb && slot < p.n_slots;
-    double s = 0.0;
+    const bool cosine = p.rule == KVCOMM_RULE_COSINE_SOFTMAX;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
     if (active) {
         if (p.gran == KVCOMM_W_TOKEN) {
-            for (int c = cl; c < p.n_chunks; c += CL) s += p.partial[((int64_t)c * p.S + slot) * p.n_sel + a];
+            for (int c = cl; c < p.n_chunks; c += CL) {
+                const int64_t i = ((int64_t)c * p.S + slot) * p.n_sel + a;
+                s0 += p.partial[i];
+                if (cosine) {
+                    s1 += p.partial[p.comp_stride + i];
+                    s2 += p.partial[2 * p.comp_stride + i];
+                }
+            }
         } else if (cl == 0) {
-            s = p.partial[slot * p.n_sel + a];  // one chunk per (layer, head): slot = chunk * S + t
+            const int64_t i = slot * p.n_sel + a;  // one chunk per (layer, head): slot = chunk * S + t
+            s0 = p.partial[i];
+            if (cosine) {
+                s1 = p.partial[p.comp_stride + i];
+                s2 = p.partial[2 * p.comp_stride + i];
+            }
         }
     }
-    for (int off = CL / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);  // lanes of a pair are adjacent
-    if (active && cl == 0) dsh[sl * p.n_sel + a] = sqrt(s);
+    for (int off = CL / 2; off >= 1; off >>= 1) {  // lanes of a pair are adjacent
+        s0 += __shfl_xor(s0, off);
+        if (cosine) {
+            s1 += __shfl_xor(s1, off);
+            s2 += __shfl_xor(s2, off);
+        }
+    }
+    if (active && cl == 0) dsh[sl * p.n_sel + a] = score_of(p, s0, s1, s2);
     __syncthreads();
     if (active && cl == 0) slot_softmax(p, dsh + sl * p.n_sel, a, slot);
 }
@@ -204,27 +315,45 @@ __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalPar
         return;
     }
     const int64_t n = (int64_t)p.n_chunks * p.S;
+    const int n_comp = p.rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
     for (int a = 0; a < p.n_sel; ++a) {
-        double s = 0.0;
-        for (int64_t i = tid; i < n; i += kBlock) s += p.partial[i * p.n_sel + a];
-        red[tid] = s;
-        __syncthreads();
-        for (int off = kBlock / 2; off >= 1; off >>= 1) {
-            if (tid < off) red[tid] += red[tid + off];
+        double tot[3] = {0.0, 0.0, 0.0};
+        for (int c = 0; c < n_comp; ++c) {
+            double s = 0.0;
+            for (int64_t i = tid; i < n; i += kBlock) s += p.partial[c * p.comp_stride + i * p.n_sel + a];
+            red[tid] = s;
+            __syncthreads();
+            for (int off = kBlock / 2; off >= 1; off >>= 1) {
+                if (tid < off) red[tid] += red[tid + off];
+                __syncthreads();
+            }
+            tot[c] = red[0];
             __syncthreads();
         }
-        if (tid == 0) dsh[a] = sqrt(red[0]);
-        __syncthreads();
+        if (tid == 0) dsh[a] = score_of(p, tot[0], tot[1], tot[2]);
     }
+    __syncthreads();
     if (tid < p.n_sel) slot_softmax(p, dsh, tid, 0);
 }
 
 template <typename T, int LPR>
-int launch_dist(const DistParams &p, int n_blocks, hipStream_t stream)
+int launch_dist(const DistParams &p, int n_blocks, bool cosine, int64_t comp_stride, hipStream_t stream)
 {
-    const int a_tiles = (p.n_sel + kAnchorTile - 1) / kAnchorTile;
-    hipLaunchKernelGGL((dist_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
+    if (cosine) {
+        const int a_tiles = (p.n_sel + kCosTile - 1) / kCosTile;
+        hipLaunchKernelGGL((cos_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p, comp_stride);
+    } else {
+        const int a_tiles = (p.n_sel + kAnchorTile - 1) / kAnchorTile;
+        hipLaunchKernelGGL((dist_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
+    }
     return launch_status();
+}
+
+int check_rule(int rule)
+{
+    return (rule == KVCOMM_RULE_L2_SOFTMAX || rule == KVCOMM_RULE_NEAREST || rule == KVCOMM_RULE_COSINE_SOFTMAX)
+               ? KVCOMM_OK
+               : KVCOMM_EINVAL;
 }
 
 }  // namespace
@@ -237,24 +366,33 @@ extern "C" size_t kvcomm_weight_slots(const kvcomm_model *model, int32_t seg_len
     return (size_t)model->n_layers * model->n_kv_heads * seg_len;
 }
 
+extern "C" size_t kvcomm_anchor_weights_rule_workspace(const kvcomm_model *model, int32_t seg_len, int32_t n_anchors,
+                                                       int32_t gran, int32_t rule)
+{
+    if (check_model(model) || check_gran(gran) || check_rule(rule) || seg_len <= 0 || n_anchors <= 0 ||
+        n_anchors > KVCOMM_MAX_ANCHORS)
+        return 0;
+    const DistPlan pl = make_plan(model, seg_len, gran);
+    const size_t n_comp = rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
+    return sizeof(double) * n_comp * (size_t)pl.n_chunks * seg_len * n_anchors;
+}
+
 extern "C" size_t kvcomm_anchor_weights_workspace(const kvcomm_model *model, int32_t seg_len, int32_t n_anchors,
                                                   int32_t gran)
 {
-    if (check_model(model) || check_gran(gran) || seg_len <= 0 || n_anchors <= 0 || n_anchors > KVCOMM_MAX_ANCHORS)
-        return 0;
-    const DistPlan pl = make_plan(model, seg_len, gran);
-    return sizeof(double) * (size_t)pl.n_chunks * seg_len * n_anchors;
+    return kvcomm_anchor_weights_rule_workspace(model, seg_len, n_anchors, gran, KVCOMM_RULE_L2_SOFTMAX);
 }
 
-extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float temperature,
-                                     kvcomm_tensor seg_base_k, int32_t seg_len, const void *const *anchor_base_k,
-                                     kvcomm_tensor anchor_layout, const int32_t *anchor_len, int32_t n_anchors,
-                                     float *weights_out, int32_t *nearest_out, int32_t *selected_out, void *workspace,
-                                     size_t workspace_bytes, void *stream)
+extern "C" int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,
+                                          kvcomm_tensor seg_base_k, int32_t seg_len,
+                                          const void *const *anchor_base_k, kvcomm_tensor anchor_layout,
+                                          const int32_t *anchor_len, int32_t n_anchors, float *weights_out,
+                                          int32_t *nearest_out, int32_t *selected_out, void *workspace,
+                                          size_t workspace_bytes, void *stream)
 {
     int st = check_model(model);
     if (st) return st;
-    if ((st = check_gran(gran))) return st;
+    if ((st = check_gran(gran)) || (st = check_rule(rule))) return st;
     if (seg_len <= 0 || n_anchors <= 0) return KVCOMM_EINVAL;
     if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
     if (!(temperature > 0.f)) return KVCOMM_EINVAL;  // also rejects NaN
@@ -273,7 +411,8 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
         fp.is_sel[a] = 1;
         dp.anc[dp.n_sel++] = anchor_base_k[a];
     }
-    const size_t need = sizeof(double) * (size_t)pl.n_chunks * seg_len * n_anchors;
+    const bool cosine = rule == KVCOMM_RULE_COSINE_SOFTMAX;
+    const size_t need = sizeof(double) * (cosine ? 3 : 1) * (size_t)pl.n_chunks * seg_len * n_anchors;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return KVCOMM_EWORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -286,21 +425,22 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
     dp.LH = model->n_layers * model->n_kv_heads;
     dp.lh_per_block = pl.lh_per_block;
     dp.n_token_tiles = pl.n_token_tiles;
+    const int64_t comp_stride = (int64_t)pl.n_chunks * seg_len * dp.n_sel;  // <= a third of the workspace
 
     if (dp.n_sel > 0) {
         const int n_blocks = pl.n_chunks * pl.n_token_tiles;
         st = KVCOMM_EUNSUPPORTED;
         if (dt == KVCOMM_BF16) {
             switch (pl.lpr) {
-                case 8: st = launch_dist<bf16_t, 8>(dp, n_blocks, s); break;
-                case 16: st = launch_dist<bf16_t, 16>(dp, n_blocks, s); break;
-                case 32: st = launch_dist<bf16_t, 32>(dp, n_blocks, s); break;
+                case 8: st = launch_dist<bf16_t, 8>(dp, n_blocks, cosine, comp_stride, s); break;
+                case 16: st = launch_dist<bf16_t, 16>(dp, n_blocks, cosine, comp_stride, s); break;
+                case 32: st = launch_dist<bf16_t, 32>(dp, n_blocks, cosine, comp_stride, s); break;
             }
         } else {
             switch (pl.lpr) {
-                case 16: st = launch_dist<float, 16>(dp, n_blocks, s); break;
-                case 32: st = launch_dist<float, 32>(dp, n_blocks, s); break;
-                case 64: st = launch_dist<float, 64>(dp, n_blocks, s); break;
+                case 16: st = launch_dist<float, 16>(dp, n_blocks, cosine, comp_stride, s); break;
+                case 32: st = launch_dist<float, 32>(dp, n_blocks, cosine, comp_stride, s); break;
+                case 64: st = launch_dist<float, 64>(dp, n_blocks, cosine, comp_stride, s); break;
             }
         }
         if (st) return st;
@@ -316,6 +456,8 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
     fp.n_anchors = n_anchors;
     fp.n_chunks = pl.n_chunks;
     fp.gran = gran;
+    fp.rule = rule;
+    fp.comp_stride = comp_stride;
     fp.tau = (double)temperature;
     if (gran == KVCOMM_W_SEGMENT) {
         hipLaunchKernelGGL(finalize_segment_kernel, dim3(1), dim3(kBlock), 0, s, fp);
@@ -329,4 +471,15 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
         hipLaunchKernelGGL(finalize_kernel, dim3(n_blocks), dim3(kBlock), 0, s, fp);
     }
     return launch_status();
+}
+
+extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float temperature,
+                                     kvcomm_tensor seg_base_k, int32_t seg_len, const void *const *anchor_base_k,
+                                     kvcomm_tensor anchor_layout, const int32_t *anchor_len, int32_t n_anchors,
+                                     float *weights_out, int32_t *nearest_out, int32_t *selected_out, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    return kvcomm_anchor_weights_rule(model, gran, KVCOMM_RULE_L2_SOFTMAX, temperature, seg_base_k, seg_len,
+                                      anchor_base_k, anchor_layout, anchor_len, n_anchors, weights_out, nearest_out,
+                                      selected_out, workspace, workspace_bytes, stream);
 }

@@ -95,6 +95,18 @@ __device__ __forceinline__ u32x4 pack<bf16_t>(const float (&in)[8])
     return r;
 }
 
+// cos / sin of the RoPE angle delta * inv_freq: product and reduction modulo 2*pi in double
+// (inv_freq = theta^(-2i/D) comes from the host in double), sine and cosine of the reduced angle in fp32.
+__device__ __forceinline__ float2 rope_cos_sin(int32_t delta, double inv_freq)
+{
+    const double x = (double)delta * inv_freq;
+    const double k = rint(x * 0.15915494309189535);  // 1 / (2 pi)
+    double red = fma(-k, 6.283185307179586, x);      // 2 pi, high part
+    red = fma(-k, 2.4492935982947064e-16, red);      // 2 pi, low part
+    const float rf = (float)red;
+    return make_float2(cosf(rf), sinf(rf));
+}
+
 // ------------------------------------------------------------------------- host-side checks
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

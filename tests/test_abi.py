@@ -38,7 +38,7 @@ def test_header_symbols_are_exported(lib):
             "kvcomm_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in kvcomm.h but not exported"
-    assert lib.kvcomm_version() >= 100
+    assert lib.kvcomm_version() >= 110
     for st in (0, -1, -2, -3, -4, 17):
         assert lib.kvcomm_status_string(st)
 
@@ -116,6 +116,48 @@ def test_workspace_and_slot_queries(lib):
     # per-(layer, head, token) weights need one partial per (layer, head)
     assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 100, 3, 1) == 8 * 4 * 100 * 3
     assert lib.kvcomm_suffix_attn_workspace(ctypes.byref(m), 100, 10) == 0
+
+
+def test_rule_predict_capture_argument_errors(lib):
+    m = _model()
+    parr = (ctypes.c_void_p * 2)(0x2000, 0x3000)
+    larr = (ctypes.c_int32 * 2)(16, 16)
+    rule = lambda r, ws_bytes=1 << 30: lib.kvcomm_anchor_weights_rule(
+        ctypes.byref(m), 0, r, 1.0, _tensor(), 16, parr, _tensor(None), larr, 2, 0x4000, None, None, 0x10000,
+        ws_bytes, None)
+    assert rule(3) == EINVAL and rule(-1) == EINVAL
+    need_l2 = lib.kvcomm_anchor_weights_rule_workspace(ctypes.byref(m), 16, 2, 0, 0)
+    need_cos = lib.kvcomm_anchor_weights_rule_workspace(ctypes.byref(m), 16, 2, 0, 2)
+    assert need_l2 == lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 16, 2, 0)
+    assert need_l2 == lib.kvcomm_anchor_weights_rule_workspace(ctypes.byref(m), 16, 2, 0, 1)
+    assert need_cos == 3 * need_l2
+    assert lib.kvcomm_anchor_weights_rule_workspace(ctypes.byref(m), 16, 2, 0, 7) == 0
+    assert rule(2, need_cos - 1) == EWORKSPACE
+
+    pred = lambda wts=0x4000, n=10, lens=(16, 16), seg_len=16, gamma=0.3, res=0x5000, ws=0x6000, ws_bytes=1 << 20: \
+        lib.kvcomm_anchor_predict(wts, n, (ctypes.c_int32 * max(len(lens), 1))(*lens), len(lens), seg_len, gamma,
+                                  None, res, ws, ws_bytes, None)
+    assert pred(wts=None) == EINVAL and pred(res=None) == EINVAL
+    assert pred(n=0) == EINVAL and pred(lens=()) == EINVAL and pred(seg_len=0) == EINVAL
+    assert pred(gamma=-0.1) == EINVAL and pred(gamma=float("nan")) == EINVAL
+    assert pred(lens=(16, -2)) == EINVAL
+    assert pred(lens=(16,) * 65) == EUNSUPPORTED
+    assert pred(ws=None) == EWORKSPACE and pred(ws=0x6004) == EWORKSPACE
+    assert lib.kvcomm_anchor_predict_workspace(10) == 8
+    assert lib.kvcomm_anchor_predict_workspace(257) == 16
+    assert lib.kvcomm_anchor_predict_workspace(10 ** 9) == 8 * 1024
+    assert lib.kvcomm_anchor_predict_workspace(0) == 0
+    assert pred(n=1000, ws_bytes=8 * 4 - 1) == EWORKSPACE
+
+    cap = lambda mm=m, seg_len=16, bk=None, out=None: lib.kvcomm_capture_offsets(
+        ctypes.byref(mm), bk or _tensor(), _tensor(0x2000), _tensor(0x3000), _tensor(0x4000), seg_len, 5,
+        out or _tensor(0x5000), _tensor(0x6000), None)
+    assert cap(seg_len=0) == EINVAL
+    assert cap(bk=_tensor(ptr=None)) == EINVAL
+    assert cap(out=_tensor(ptr=0x5008)) == EINVAL
+    assert cap(mm=_model(head_dim=72)) == EUNSUPPORTED
+    assert lib.kvcomm_capture_offsets(None, _tensor(), _tensor(), _tensor(), _tensor(), 16, 0, _tensor(), _tensor(),
+                                      None) == EINVAL
 
 
 def _align(lib, m, gran=0, seg_len=16, ptrs=(0x2000,), lens=(16,), weights=0x4000, bk=None, out=None, adp=None):

@@ -1,0 +1,244 @@
+"""GPU parity of the rows beyond the reuse step proper: weighting variants (nearest, cosine),
+anchor prediction (Eq. "pred") and offset capture (fallback branch of Algorithm 1), through
+the C ABI against the float64 oracle.  Integers bit-exact, floats to tests/parity.py's rules.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_12872_amd as kv
+from paper_2510_12872_amd import hotpath, workloads
+from paper_2510_12872_amd.workloads import scaled
+
+from parity import check_close, check_weights, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+SMALL_BF16 = scaled(workloads.LLAMA8B_5AGENTS, name="small_bf16", n_layers=3, n_kv_heads=2, n_q_heads=8,
+                    n_agents=1, prefix_len=37, seg_len=203, n_segments=1, n_anchors=5, tq=0)
+SMALL_F32 = scaled(workloads.TINY, name="small_f32", seg_len=77, prefix_len=5, tq=0, n_anchors=3)
+RAGGED = scaled(SMALL_BF16, name="ragged", n_anchors=11, seg_len=50,
+                anchor_lens=(49, 50, 64, 10, 50, 50, 50, 60, 50, 50, 50))
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def oracle_inputs(seg):
+    S = seg.base_k.shape[2]
+    anc = [to_np(a) if n >= S else np.zeros(seg.base_k.shape[:2] + (0, seg.base_k.shape[3]))
+           for a, n in zip(seg.anchor_k, seg.anchor_len)]
+    return to_np(seg.base_k), anc
+
+
+# ------------------------------------------------------------------------- weighting variants
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32, RAGGED], ids=lambda w: w.name)
+@pytest.mark.parametrize("gran", [kv.W_TOKEN, kv.W_LAYER_HEAD_TOKEN, kv.W_SEGMENT])
+def test_nearest_and_cosine_rules(w, gran):
+    say(f"rules {w.name} gran={gran}")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    if w is RAGGED:   # what must never be read
+        seg.anchor_k[0][:, :, 49:] = float("nan")
+        seg.anchor_k[3][:, :, 10:] = float("nan")
+    bk, anc = oracle_inputs(seg)
+    dist, sel = oracle.distances(bk, anc, gran)
+    # default rule through the new entry point == the original entry point, bit for bit
+    w0, n0, s0 = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len, 0.7, gran)
+    w1, n1, s1 = kv.kvcomm_anchor_weights_rule(model, kv.RULE_L2_SOFTMAX, seg.base_k, seg.anchor_k, seg.anchor_len,
+                                               0.7, gran)
+    torch.cuda.synchronize()
+    assert torch.equal(w0, w1) and torch.equal(n0, n1) and torch.equal(s0, s1)
+    want, near = oracle.weights(dist, sel, 0.7)
+    check_weights(w1.cpu().numpy(), want.T)
+    assert np.array_equal(n1.cpu().numpy(), near)
+    # nearest
+    wn, nn, sn = kv.kvcomm_anchor_weights_rule(model, kv.RULE_NEAREST, seg.base_k, seg.anchor_k, seg.anchor_len,
+                                               1.0, gran)
+    torch.cuda.synchronize()
+    want, near = oracle.weights_nearest(dist, sel)
+    assert np.array_equal(sn.cpu().numpy(), sel)
+    assert np.array_equal(nn.cpu().numpy(), near)
+    assert np.array_equal(wn.cpu().numpy(), want.T.astype(np.float32))      # one-hot: exact
+    # cosine
+    for tau in (1.0, 0.05):
+        wc, nc, sc = kv.kvcomm_anchor_weights_rule(model, kv.RULE_COSINE_SOFTMAX, seg.base_k, seg.anchor_k,
+                                                   seg.anchor_len, tau, gran)
+        torch.cuda.synchronize()
+        sim, sel_c = oracle.cosine(bk, anc, gran)
+        want, best = oracle.weights_from_sim(sim, sel_c, tau)
+        assert np.array_equal(sc.cpu().numpy(), sel_c)
+        assert np.array_equal(nc.cpu().numpy(), best)
+        check_weights(wc.cpu().numpy(), want.T, "cosine weights")
+
+
+def test_rules_with_duplicate_and_identical_anchors():
+    w = scaled(SMALL_BF16, n_anchors=4, seg_len=33)
+    say("rules ties")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    seg.anchor_k[2] = seg.anchor_k[1].clone()          # exact tie between 1 and 2
+    seg.anchor_k[3] = seg.base_k.clone()               # identical to the sample
+    wn, nn, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_NEAREST, seg.base_k, seg.anchor_k, seg.anchor_len)
+    wc, nc, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_COSINE_SOFTMAX, seg.base_k, seg.anchor_k, seg.anchor_len,
+                                              0.01)
+    torch.cuda.synchronize()
+    assert torch.all(nn == 3) and torch.all(wn[:, 3] == 1) and torch.all(wn[:, :3] == 0)
+    assert torch.all(nc == 3) and torch.all(wc[:, 3] > 0.999)
+    assert torch.equal(wc[:, 1], wc[:, 2])
+    seg.anchor_k[3] = seg.anchor_k[0].clone()          # ties 0 == 3 and 1 == 2: lowest index wins
+    wn, nn, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_NEAREST, seg.base_k, seg.anchor_k, seg.anchor_len)
+    torch.cuda.synchronize()
+    bk, anc = oracle_inputs(seg)
+    dist, sel = oracle.distances(bk, anc)
+    _, near = oracle.weights_nearest(dist, sel)
+    assert np.array_equal(nn.cpu().numpy(), near) and set(near.tolist()) <= {0, 1}
+
+
+def test_nearest_rule_feeds_align():
+    """Nearest-anchor approximation end to end: K^ = R K + R dK_nearest, V^ = V + dV_nearest."""
+    w = scaled(SMALL_BF16, n_anchors=6, seg_len=70)
+    say("nearest -> align")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    wn, nn, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_NEAREST, seg.base_k, seg.anchor_k, seg.anchor_len)
+    ok, ov = torch.empty_like(seg.base_k), torch.empty_like(seg.base_v)
+    kv.kvcomm_align_kv(model, seg.base_k, seg.base_v, seg.anchor_dk, seg.anchor_dv, wn, seg.delta_pos, ok, ov,
+                       seg.anchor_len)
+    torch.cuda.synchronize()
+    bk, anc = oracle_inputs(seg)
+    dist, sel = oracle.distances(bk, anc)
+    wo, _ = oracle.weights_nearest(dist, sel)
+    rk, rv = oracle.align(bk, to_np(seg.base_v), [to_np(a) for a in seg.anchor_dk], [to_np(a) for a in seg.anchor_dv],
+                          wo, seg.delta_pos, w.rope_theta)
+    check_close(to_np(ok), rk, w.dtype, "K^ nearest")
+    check_close(to_np(ov), rv, w.dtype, "V^ nearest")
+
+
+def test_rule_full_size_sampled_tokens():
+    """Config-2 segment at full size, cosine and nearest, oracle on sampled tokens (tokens are independent)."""
+    w = scaled(workloads.LLAMA8B_5AGENTS, n_agents=1, n_segments=1)
+    say("rules full size")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    tokens = [0, 1, 255, 256, 300, 511]
+    idx = torch.as_tensor(tokens, device=DEV)
+    bk = to_np(seg.base_k[:, :, idx])
+    anc = [to_np(a[:, :, idx]) for a in seg.anchor_k]
+    wc, nc, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_COSINE_SOFTMAX, seg.base_k, seg.anchor_k, seg.anchor_len)
+    wn, nn, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_NEAREST, seg.base_k, seg.anchor_k, seg.anchor_len)
+    torch.cuda.synchronize()
+    sim, sel = oracle.cosine(bk, anc)
+    want, best = oracle.weights_from_sim(sim, sel, 1.0)
+    check_weights(wc.cpu().numpy()[tokens], want.T, "cosine weights")
+    assert np.array_equal(nc.cpu().numpy()[tokens], best)
+    dist, sel = oracle.distances(bk, anc)
+    want, near = oracle.weights_nearest(dist, sel)
+    assert np.array_equal(nn.cpu().numpy()[tokens], near)
+    assert np.array_equal(wn.cpu().numpy()[tokens], want.T.astype(np.float32))
+
+
+# ------------------------------------------------------------------------- anchor prediction
+@pytest.mark.parametrize("n_slots", [1, 7, 256, 1000, 300001])
+def test_predict_on_seeded_weights(n_slots):
+    say(f"predict n={n_slots}")
+    g = torch.Generator().manual_seed(n_slots)
+    A = 6
+    wts = torch.softmax(torch.randn((n_slots, A), generator=g) * 2.0, dim=1).to(torch.float32)
+    lens = [40, 50, 64, 50, 10, 50]
+    wts[:, [0, 4]] = 0.0                                   # unselected anchors carry no weight
+    wts = (wts / wts.sum(1, keepdim=True)).contiguous()
+    sel = np.array([int(x >= 50) for x in lens], dtype=np.intc)
+    new_o, ent_o, mean_o = oracle.predict(wts.numpy().T, sel, lens, 50, 0.0)
+    res, ent = kv.kvcomm_anchor_predict(wts.to(DEV), lens, 50, 0.3, want_entropy=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(ent.cpu().numpy(), ent_o, atol=1e-5)
+    assert abs(float(res[1]) - mean_o) <= 1e-5
+    # decisions for thresholds well on either side of the mean entropy
+    for gamma in (0.0, 0.5 * mean_o / np.log(4), 1.5 * mean_o / np.log(4), 10.0):
+        gamma = float(np.float32(gamma))
+        want = oracle.predict(wts.numpy().T, sel, lens, 50, gamma)[0]
+        got = kv.kvcomm_anchor_predict(wts.to(DEV), lens, 50, gamma)
+        torch.cuda.synchronize()
+        assert int(got[0]) == want, gamma
+    # longer than every anchor / no candidate: new anchor whatever the weights
+    assert int(kv.kvcomm_anchor_predict(wts.to(DEV), lens, 65, 10.0)[0]) == 1 == oracle.predict(
+        wts.numpy().T, np.zeros(A, dtype=np.intc), lens, 65, 10.0)[0]
+
+
+def test_predict_closed_forms_and_chain():
+    say("predict closed forms")
+    A = 4
+    uni = torch.full((3, A), 0.25, device=DEV)
+    res, ent = kv.kvcomm_anchor_predict(uni, [8] * A, 8, 0.99, want_entropy=True)
+    assert int(res[0]) == 1 and abs(float(res[1]) - np.log(4)) < 1e-6
+    assert int(kv.kvcomm_anchor_predict(uni, [8] * A, 8, 1.01)[0]) == 0
+    hot = torch.zeros((3, A), device=DEV)
+    hot[:, 2] = 1.0
+    res = kv.kvcomm_anchor_predict(hot, [8] * A, 8, 0.3)
+    assert int(res[0]) == 0 and float(res[1]) == 0.0
+    # chained with the device weights: segment granularity = the paper's scalar case
+    w = scaled(SMALL_BF16, n_anchors=5, seg_len=64)
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    for gran in (kv.W_SEGMENT, kv.W_TOKEN):
+        wd, _, _ = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len, 1.0, gran)
+        res = kv.kvcomm_anchor_predict(wd, seg.anchor_len, w.seg_len, 0.3)
+        torch.cuda.synchronize()
+        bk, anc = oracle_inputs(seg)
+        dist, sel = oracle.distances(bk, anc, gran)
+        wo, _ = oracle.weights(dist, sel, 1.0)
+        new, _, mean = oracle.predict(wo, sel, seg.anchor_len, w.seg_len, float(np.float32(0.3)))
+        assert abs(float(res[1]) - mean) < 1e-4
+        if abs(mean - 0.3 * np.log(5)) > 1e-3:
+            assert int(res[0]) == new
+
+
+# ------------------------------------------------------------------------- offset capture
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32, scaled(SMALL_BF16, name="bf16_d64", head_dim=64, n_q_heads=2)],
+                         ids=lambda w: w.name)
+@pytest.mark.parametrize("delta", [0, 300, 131071])
+def test_capture_offsets(w, delta):
+    say(f"capture {w.name} delta={delta}")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    # "real" cache of a dense prefill: an independent N(0,1) draw (any tensor exercises the arithmetic);
+    # the offsets then stay below 8 in magnitude, where half a bf16 ulp is within the 2e-2 bound
+    g = torch.Generator(device=DEV).manual_seed(1234 + delta)
+    shape = seg.base_k.shape
+    real_k = torch.randn(shape, generator=g, device=DEV).to(w.dtype)
+    real_v = torch.randn(shape, generator=g, device=DEV).to(w.dtype)
+    # real tensors as strided views into a longer cache, as in the agent's cache
+    cache_k = torch.zeros(shape[:2] + (shape[2] + 24, shape[3]), dtype=w.dtype, device=DEV)
+    cache_v = torch.zeros_like(cache_k)
+    cache_k[:, :, 8:8 + shape[2]] = real_k
+    cache_v[:, :, 8:8 + shape[2]] = real_v
+    dk, dv = kv.kvcomm_capture_offsets(model, seg.base_k, seg.base_v, cache_k[:, :, 8:8 + shape[2]],
+                                       cache_v[:, :, 8:8 + shape[2]], delta)
+    torch.cuda.synchronize()
+    want_k, want_v = oracle.capture(to_np(seg.base_k), to_np(seg.base_v), to_np(real_k), to_np(real_v), delta,
+                                    w.rope_theta)
+    check_close(to_np(dk), want_k, w.dtype, "dK")
+    check_close(to_np(dv), want_v, w.dtype, "dV")
+    if delta == 0 and w.dtype == torch.float32:
+        assert torch.equal(dk, real_k - seg.base_k) and torch.equal(dv, real_v - seg.base_v)
+
+
+def test_capture_then_align_reproduces_real_cache_fp32():
+    """A captured anchor of weight 1 gives back the real cache (round trip through both kernels)."""
+    w = scaled(SMALL_F32, seg_len=61)
+    say("capture round trip")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    real_k = torch.randn(seg.base_k.shape, generator=g, device=DEV)
+    real_v = torch.randn(seg.base_k.shape, generator=g, device=DEV)
+    dk, dv = kv.kvcomm_capture_offsets(model, seg.base_k, seg.base_v, real_k, real_v, 777)
+    ones = torch.ones((w.seg_len, 1), device=DEV)
+    ok, ov = torch.empty_like(real_k), torch.empty_like(real_v)
+    kv.kvcomm_align_kv(model, seg.base_k, seg.base_v, [dk], [dv], ones, 777, ok, ov)
+    torch.cuda.synchronize()
+    assert float((ok - real_k).abs().max()) < 1e-5 and float((ov - real_v).abs().max()) < 1e-6
