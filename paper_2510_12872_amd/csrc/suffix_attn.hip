@@ -12,7 +12,8 @@
 //     scalar, and the exponentiated scores are already laid out as the B operand of the second
 //     product (the key order inside a 16-key step is a fixed permutation, matched on the V side).
 //   * K and V tiles travel global -> LDS with global_load_lds_dwordx4 (no registers, no LDS
-//     stores); the XOR swizzle of 16-byte chunks that keeps operand reads bank-conflict free is
+//     stores), issued through inline assembly with a scalar row base and a fixed per-lane offset;
+//     the XOR swizzle of 16-byte chunks that keeps operand reads bank-conflict free is
 //     applied by choosing which global chunk each lane fetches.  K operands are read with
 //     ds_read_b128; V^T operands with ds_read_b64_tr_b16, which transposes on the way out of
 //     LDS, so V is never transposed by the vector ALU.
@@ -59,7 +60,6 @@ struct AttnParams {
 #define KVC_ATTN_NW 4
 #endif
 
-constexpr int kKT = 64;  // keys per LDS tile
 constexpr float kLazyLog2 = 8.f;  // the softmax reference maximum lags the true one by at most 2^8
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -77,6 +77,29 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
+}
+
+// One wavefront-wide direct load global -> LDS (global_load_lds_dwordx4): lane i moves the 16 bytes at
+// its own global address `src` to LDS address `dst` + 16 * i (`dst` is wavefront-uniform and travels in M0).
+// Written as inline assembly on purpose: the compiler then does not know of the pending LDS write and
+// inserts no wait of its own before later LDS reads (it would wait for ALL outstanding loads ahead of the
+// first transposing read and so serialise the prefetch).  Ordering is explicit instead: tile_barrier()
+// waits for the loads (vmcnt) and synchronises the block before anybody reads what they wrote.
+// M0 is a reserved register that the compiler itself only ever sets immediately before an instruction
+// that consumes it, so overwriting it here disturbs nothing (nothing else in this file uses it).
+__device__ __forceinline__ void dma16(const unsigned char *src, const lds_byte *dst)
+{
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0) : "memory");
+}
+
+// The same with a wavefront-uniform 64-bit base (scalar registers) plus a per-lane 32-bit byte offset: the
+// steady-state loads then cost no vector ALU instruction (the row base advances on the scalar unit and
+// the per-lane offset never changes).
+__device__ __forceinline__ void dma16_sbase(const unsigned char *base, uint32_t voff, const lds_byte *dst)
+{
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory");
 }
 
 template <int D, int NW, int QB, int WPE>
@@ -190,22 +213,18 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 32 * h + rbase + it * RPL;  // wavefront-uniform
-            const unsigned char *src = kbytes + (int64_t)row0 * p.s_k.token * 2 + ld_koff[it];
-            if (clamp) src = kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB),
-                                             16, 0, 0);
+            const lds_byte *dst = kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB;
+            if (clamp) dma16(kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it), dst);
+            else dma16_sbase(kbytes + (int64_t)row0 * p.s_k.token * 2, ld_koff[it], dst);
         }
     };
     auto load_v64 = [&](int tile, bool clamp) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 64 * tile + wave * RW + it * RPL;
-            const unsigned char *src = vbytes + (int64_t)row0 * p.s_v.token * 2 + ld_voff[it];
-            if (clamp) src = vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB),
-                                             16, 0, 0);
+            const lds_byte *dst = vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB;
+            if (clamp) dma16(vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it), dst);
+            else dma16_sbase(vbytes + (int64_t)row0 * p.s_v.token * 2, ld_voff[it], dst);
         }
     };
 
