@@ -77,8 +77,10 @@ def cpu_baseline(w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    # the shader clock of an idle MI355X needs some tens of milliseconds of load to settle: ten warm-up
+    # steps (about 80 ms) put the timed region at the sustained clock
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -46,6 +46,7 @@ extern "C" {
 #endif
 
 #define KVCOMM_MAX_ANCHORS 64
+#define KVCOMM_MAX_BATCH 8   /* segments per batched launch */
 
 typedef enum {
     KVCOMM_OK = 0,
@@ -150,6 +151,33 @@ int kvcomm_align_kv(const kvcomm_model *model, int32_t gran,
                     kvcomm_tensor out_k, kvcomm_tensor out_v, void *stream);
 
 /* --------------------------------------------------------------------------------------
+ * The same update for several segments in ONE launch (the reuse branch of Algorithm 1 treats
+ * the placeholders of a prompt, and the prefix segments that follow them (Eq. "pf_update"),
+ * independently and "in parallel").  Job j has exactly the arguments of kvcomm_align_kv; all
+ * jobs share `anchor_layout` and the weight granularity.  For a prefix segment pass its own
+ * base cache and stored deviations with the PLACEHOLDER's weights: per-segment weights
+ * (KVCOMM_W_SEGMENT) apply to a segment of any length, per-token weights need equal lengths.
+ * Limits: n_jobs <= KVCOMM_MAX_BATCH; over all jobs at most KVCOMM_MAX_ANCHORS selected anchors
+ * and KVCOMM_MAX_ANCHORS + 1 distinct rotations; beyond them KVCOMM_EUNSUPPORTED (split the call).
+ * Results are bit-identical to n_jobs separate kvcomm_align_kv calls.  Outputs of different
+ * jobs must not overlap.                                                                  */
+typedef struct {
+    kvcomm_tensor base_k, base_v;       /* [L, Hkv, seg_len, D] */
+    kvcomm_tensor out_k, out_v;
+    int32_t seg_len;
+    int32_t delta_pos;
+    const void *const *anchor_dk;       /* HOST [n_anchors] of DEVICE pointers */
+    const void *const *anchor_dv;
+    const int32_t *anchor_len;          /* HOST [n_anchors] */
+    const int32_t *anchor_delta_pos;    /* HOST [n_anchors] or NULL */
+    int32_t n_anchors;
+    const float *weights;               /* DEVICE [n, n_anchors] */
+} kvcomm_align_job;
+
+int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
+                          const kvcomm_align_job *jobs, int32_t n_jobs, void *stream);
+
+/* --------------------------------------------------------------------------------------
  * Causal attention of the tq non-shared suffix queries over the assembled cache (workflow
  * step 4; q, k, v as defined in Sec. 3.1).  Suffix query i sits at cache position
  * n_ctx + i and attends to cache tokens 0 .. n_ctx + i:
@@ -195,6 +223,33 @@ int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gran, int32_t 
                                const int32_t *anchor_len, int32_t n_anchors,
                                float *weights_out, int32_t *nearest_out, int32_t *selected_out,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------------------
+ * Anchor matching of several segments in ONE launch of each stage (see kvcomm_align_kv_batch for
+ * the reason).  Job j has the per-segment arguments of kvcomm_anchor_weights_rule; all jobs share
+ * `anchor_layout`, the granularity, the rule and the temperature.  The workspace holds
+ * kvcomm_anchor_weights_batch_workspace() bytes for the same segment lengths and pool sizes.
+ * Limits: n_jobs <= KVCOMM_MAX_BATCH and at most KVCOMM_MAX_ANCHORS selected anchors over all jobs
+ * (else KVCOMM_EUNSUPPORTED).  Each segment's result is what the single-segment call would give up
+ * to the rounding of the double-precision partial sums (the cut into chunks may differ).        */
+typedef struct {
+    kvcomm_tensor seg_base_k;           /* [L, Hkv, seg_len, D] */
+    int32_t seg_len;
+    const void *const *anchor_base_k;   /* HOST [n_anchors] of DEVICE pointers */
+    const int32_t *anchor_len;          /* HOST [n_anchors] */
+    int32_t n_anchors;
+    float *weights_out;                 /* DEVICE [n, n_anchors] */
+    int32_t *nearest_out;               /* DEVICE [n] or NULL */
+    int32_t *selected_out;              /* DEVICE [n_anchors] or NULL */
+} kvcomm_weights_job;
+
+size_t kvcomm_anchor_weights_batch_workspace(const kvcomm_model *model, int32_t gran, int32_t rule,
+                                             const int32_t *seg_lens, const int32_t *n_anchors,
+                                             int32_t n_jobs);
+
+int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,
+                                kvcomm_tensor anchor_layout, const kvcomm_weights_job *jobs, int32_t n_jobs,
+                                void *workspace, size_t workspace_bytes, void *stream);
 
 /* --------------------------------------------------------------------------------------
  * Anchor prediction (Eq. "pred"): should a sample become a new anchor?  Yes (1) when it is

@@ -18,6 +18,7 @@ W_TOKEN = 0
 W_LAYER_HEAD_TOKEN = 1
 W_SEGMENT = 2
 MAX_ANCHORS = 64
+MAX_BATCH = 8
 RULE_L2_SOFTMAX = 0
 RULE_NEAREST = 1
 RULE_COSINE_SOFTMAX = 2
@@ -39,6 +40,21 @@ class _CModel(ctypes.Structure):
 class _CTensor(ctypes.Structure):
     _fields_ = [("ptr", ctypes.c_void_p), ("stride_layer", ctypes.c_int64), ("stride_head", ctypes.c_int64),
                 ("stride_token", ctypes.c_int64)]
+
+
+class _CAlignJob(ctypes.Structure):
+    _fields_ = [("base_k", _CTensor), ("base_v", _CTensor), ("out_k", _CTensor), ("out_v", _CTensor),
+                ("seg_len", ctypes.c_int32), ("delta_pos", ctypes.c_int32),
+                ("anchor_dk", ctypes.POINTER(ctypes.c_void_p)), ("anchor_dv", ctypes.POINTER(ctypes.c_void_p)),
+                ("anchor_len", ctypes.POINTER(ctypes.c_int32)), ("anchor_delta_pos", ctypes.POINTER(ctypes.c_int32)),
+                ("n_anchors", ctypes.c_int32), ("weights", ctypes.c_void_p)]
+
+
+class _CWeightsJob(ctypes.Structure):
+    _fields_ = [("seg_base_k", _CTensor), ("seg_len", ctypes.c_int32),
+                ("anchor_base_k", ctypes.POINTER(ctypes.c_void_p)), ("anchor_len", ctypes.POINTER(ctypes.c_int32)),
+                ("n_anchors", ctypes.c_int32), ("weights_out", ctypes.c_void_p), ("nearest_out", ctypes.c_void_p),
+                ("selected_out", ctypes.c_void_p)]
 
 
 @dataclass(frozen=True)
@@ -103,6 +119,13 @@ def load_library():
     lib.kvcomm_capture_offsets.argtypes = [mp, _CTensor, _CTensor, _CTensor, _CTensor, i32, i32, _CTensor, _CTensor,
                                            vp]
     lib.kvcomm_capture_offsets.restype = ctypes.c_int
+    lib.kvcomm_align_kv_batch.argtypes = [mp, i32, _CTensor, ctypes.POINTER(_CAlignJob), i32, vp]
+    lib.kvcomm_align_kv_batch.restype = ctypes.c_int
+    lib.kvcomm_anchor_weights_batch_workspace.argtypes = [mp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), i32]
+    lib.kvcomm_anchor_weights_batch_workspace.restype = sz
+    lib.kvcomm_anchor_weights_batch.argtypes = [mp, i32, i32, f32, _CTensor, ctypes.POINTER(_CWeightsJob), i32, vp,
+                                                sz, vp]
+    lib.kvcomm_anchor_weights_batch.restype = ctypes.c_int
     lib.kvcomm_status_string.argtypes = [ctypes.c_int]
     lib.kvcomm_status_string.restype = ctypes.c_char_p
     lib.kvcomm_version.argtypes = []
@@ -305,3 +328,99 @@ def kvcomm_capture_offsets(model, base_k, base_v, real_k, real_v, delta_pos, out
                                       d(real_k, "real_k"), d(real_v, "real_v"), seg_len, int(delta_pos),
                                       d(out_dk, "out_dk"), d(out_dv, "out_dv"), _stream_ptr(stream)))
     return out_dk, out_dv
+
+
+def _same_layout(a, b):
+    return (a.stride_layer, a.stride_head, a.stride_token) == (b.stride_layer, b.stride_head, b.stride_token)
+
+
+def kvcomm_anchor_weights_batch_workspace(model, seg_lens, n_anchors, gran=W_TOKEN, rule=RULE_L2_SOFTMAX):
+    n = len(seg_lens)
+    sl = (ctypes.c_int32 * n)(*[int(x) for x in seg_lens])
+    na = (ctypes.c_int32 * n)(*[int(x) for x in n_anchors])
+    return int(load_library().kvcomm_anchor_weights_batch_workspace(ctypes.byref(model.c()), gran, rule, sl, na, n))
+
+
+def kvcomm_anchor_weights_batch(model, jobs, temperature=1.0, gran=W_TOKEN, rule=RULE_L2_SOFTMAX, workspace=None,
+                                stream=None):
+    """Anchor matching of several segments in one launch per stage.
+
+    jobs: list of dicts with seg_base_k, anchor_base_k (list of tensors) and optionally anchor_len,
+    weights_out, nearest_out, selected_out.  Returns a list of (weights, nearest, selected)."""
+    lib = load_library()
+    n = len(jobs)
+    cjobs = (_CWeightsJob * max(n, 1))()
+    keep, outs, layout = [], [], None
+    for j, jd in enumerate(jobs):
+        seg = jd["seg_base_k"]
+        S, A, dev = seg.shape[2], len(jd["anchor_base_k"]), seg.device
+        slots = kvcomm_weight_slots(model, S, gran)
+        w = jd.get("weights_out")
+        w = torch.empty((slots, A), dtype=torch.float32, device=dev) if w is None else w
+        nr = jd.get("nearest_out")
+        nr = torch.empty((slots,), dtype=torch.int32, device=dev) if nr is None else nr
+        so = jd.get("selected_out")
+        so = torch.empty((A,), dtype=torch.int32, device=dev) if so is None else so
+        ptrs, lay, lens = _anchor_args(jd["anchor_base_k"], jd.get("anchor_len"), model.dtype, "anchor_base_k")
+        if layout is None:
+            layout = lay
+        elif A and not _same_layout(layout, lay):
+            raise KVCommError(-1, "all anchors of a batched call must share one layout")
+        keep.append((ptrs, lens))
+        cjobs[j] = _CWeightsJob(_desc(seg, model.dtype, "seg_base_k"), S, ptrs, lens, A, w.data_ptr(), nr.data_ptr(),
+                                so.data_ptr())
+        outs.append((w, nr, so))
+    if workspace is None:
+        need = kvcomm_anchor_weights_batch_workspace(model, [jd["seg_base_k"].shape[2] for jd in jobs],
+                                                     [len(jd["anchor_base_k"]) for jd in jobs], gran, rule)
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=jobs[0]["seg_base_k"].device)
+    _check(lib.kvcomm_anchor_weights_batch(ctypes.byref(model.c()), gran, int(rule), float(temperature),
+                                           layout if layout is not None else _CTensor(None, 0, 0, 0), cjobs, n,
+                                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                           _stream_ptr(stream)))
+    return outs
+
+
+def kvcomm_align_kv_batch(model, jobs, gran=W_TOKEN, stream=None):
+    """Positional alignment + offset approximation of several segments in one launch.
+
+    jobs: list of dicts with base_k, base_v, anchor_dk, anchor_dv (lists of tensors), weights, delta_pos,
+    out_k, out_v and optionally anchor_len, anchor_delta_pos."""
+    lib = load_library()
+    n = len(jobs)
+    cjobs = (_CAlignJob * max(n, 1))()
+    keep, layout = [], None
+    for j, jd in enumerate(jobs):
+        A = len(jd["anchor_dk"])
+        if len(jd["anchor_dv"]) != A:
+            raise KVCommError(-1, "anchor_dk and anchor_dv differ in length")
+        pk, lay, lens = _anchor_args(jd["anchor_dk"], jd.get("anchor_len"), model.dtype, "anchor_dk")
+        pv, lay_v, _ = _anchor_args(jd["anchor_dv"], jd.get("anchor_len"), model.dtype, "anchor_dv")
+        if A:
+            if not _same_layout(lay, lay_v) or (layout is not None and not _same_layout(layout, lay)):
+                raise KVCommError(-1, "all anchors of a batched call must share one layout")
+            layout = lay
+        adp = None
+        if jd.get("anchor_delta_pos") is not None:
+            if len(jd["anchor_delta_pos"]) != A:
+                raise KVCommError(-1, "anchor_delta_pos must have one entry per anchor")
+            adp = (ctypes.c_int32 * max(A, 1))(*[int(x) for x in jd["anchor_delta_pos"]])
+        w = jd.get("weights")
+        S = jd["base_k"].shape[2]
+        if A:
+            if w is None or w.dtype != torch.float32 or not w.is_contiguous():
+                raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
+            if gran == W_SEGMENT:
+                ok = w.numel() == A
+            else:
+                ok = w.numel() == kvcomm_weight_slots(model, S, gran) * A
+            if not ok:
+                raise KVCommError(-1, "weights: wrong number of elements for this granularity")
+        keep.append((pk, pv, lens, adp))
+        d = lambda t, what: _desc(t, model.dtype, what)
+        cjobs[j] = _CAlignJob(d(jd["base_k"], "base_k"), d(jd["base_v"], "base_v"), d(jd["out_k"], "out_k"),
+                              d(jd["out_v"], "out_v"), S, int(jd["delta_pos"]), pk, pv, lens, adp, A,
+                              None if w is None else w.data_ptr())
+    _check(lib.kvcomm_align_kv_batch(ctypes.byref(model.c()), gran,
+                                     layout if layout is not None else _CTensor(None, 0, 0, 0), cjobs, n,
+                                     _stream_ptr(stream)))

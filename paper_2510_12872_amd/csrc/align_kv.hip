@@ -25,28 +25,49 @@ namespace {
 
 using namespace kvc;
 
+#ifndef KVC_ALIGN_BLOCKS
+#define KVC_ALIGN_BLOCKS 32768  // blocks per tensor the grid aims at (measured best on MI355X)
+#endif
+
+#ifndef KVC_ALIGN_INFLIGHT
+#define KVC_ALIGN_INFLIGHT 4
+#endif
+
 constexpr int kBlock = 256;
+constexpr int kAnchorsInFlight = KVC_ALIGN_INFLIGHT;
 constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
 constexpr int kMaxHalf = 128;  // head_dim / 2 for the largest supported head_dim
 
-struct AlignParams {
+// One segment of a launch.  A launch covers up to KVCOMM_MAX_BATCH segments (all placeholders of an
+// agent, and the prefix segments that follow them, are independent and are updated "in parallel").
+struct AlignJob {
     const void *base[2];   // [0] keys, [1] values
     void *out[2];
-    Strides s_base[2], s_out[2], s_anc;
+    Strides s_base[2], s_out[2];
     const float *weights;
-    int32_t H, S, LH;          // kv heads, tokens, layers*heads
-    int32_t w_pitch;           // anchors per weight row (n_anchors of the call)
-    int32_t n_sel;             // selected anchors (compacted below)
-    int32_t gran;
-    int32_t lh_per_block, n_token_tiles;
-    int32_t n_tab;             // rotation tables built per block
-    int32_t base_tab;          // table of the base keys' rotation + 1, 0 = identity
-    int32_t tab_delta[kMaxTab];                 // position delta of each table
-    const void *anc[2][KVCOMM_MAX_ANCHORS];     // [0] dK, [1] dV of the selected anchors, original order
-    uint8_t col[KVCOMM_MAX_ANCHORS];            // weight column of selected anchor
-    uint8_t tab[KVCOMM_MAX_ANCHORS];            // its rotation table + 1, 0 = identity
+    int32_t S;                 // tokens
+    int32_t w_pitch;           // anchors per weight row (n_anchors of the segment)
+    int32_t n_token_tiles;
+    int32_t block0;            // first blockIdx.x of the segment
+    int16_t a0, n_sel;         // its selected anchors: entries [a0, a0 + n_sel) of anc / col / tab
+    int16_t t0, n_tab;         // its rotation tables: entries [t0, t0 + n_tab) of tab_delta
+    int16_t base_tab;          // table of the base keys' rotation (index among the segment's tables) + 1, 0 = identity
+    int16_t pad_;
+};
+
+struct AlignParams {
+    AlignJob job[KVCOMM_MAX_BATCH];
+    Strides s_anc;
+    int32_t H, LH;             // kv heads, layers*heads
+    int32_t gran, n_jobs;
+    int32_t lh_per_block;
+    int32_t tab_delta[kMaxTab];                 // position delta of each rotation table
+    const void *anc[2][KVCOMM_MAX_ANCHORS];     // [0] dK, [1] dV of the selected anchors of all segments
+    uint8_t col[KVCOMM_MAX_ANCHORS];            // weight column of a selected anchor
+    uint8_t tab[KVCOMM_MAX_ANCHORS];            // its rotation table (index among the segment's tables) + 1, 0 = identity
     double inv_freq[kMaxHalf];                  // theta^(-2i/D), i < D/2
 };
+static_assert(sizeof(AlignParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 template <typename T, int LPR>
 __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
@@ -55,54 +76,62 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
     constexpr int HALF = LPR * EPV;  // D / 2
     constexpr int RPB = kBlock / LPR;
 
+    int ji = 0;
+#pragma unroll
+    for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
+        if (i < p.n_jobs && (int)blockIdx.x >= p.job[i].block0) ji = i;
+    const AlignJob &jb = p.job[ji];
+    const int n_sel = jb.n_sel, a0 = jb.a0;
+
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float2 *cs = reinterpret_cast<float2 *>(smem_raw);                          // [n_tab][HALF] (cos, sin)
-    float *w_lds = reinterpret_cast<float *>(smem_raw) + 2 * p.n_tab * HALF;    // [RPB][n_sel]
+    float *w_lds = reinterpret_cast<float *>(smem_raw) + 2 * jb.n_tab * HALF;   // [RPB][n_sel]
 
     const int tid = threadIdx.x;
     const int row = tid / LPR;
     const int lir = tid % LPR;
-    const int tile = blockIdx.x % p.n_token_tiles;
-    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int bx = blockIdx.x - jb.block0;
+    const int tile = bx % jb.n_token_tiles;
+    const int chunk = bx / jb.n_token_tiles;
     const int which = blockIdx.y;          // 0 = keys (rotated), 1 = values
     const bool is_k = which == 0;
     const int t = tile * RPB + row;
-    const bool valid = t < p.S;
+    const bool valid = t < jb.S;
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
     if (is_k) {
         // cos/sin of delta * theta^(-2i/D): product and reduction modulo 2*pi in double.
-        for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock) {
+        for (int idx = tid; idx < jb.n_tab * HALF; idx += kBlock) {
             const int r = idx / HALF, i = idx % HALF;
-            cs[idx] = rope_cos_sin(p.tab_delta[r], p.inv_freq[i]);
+            cs[idx] = rope_cos_sin(p.tab_delta[jb.t0 + r], p.inv_freq[i]);
         }
     }
     if (p.gran != KVCOMM_W_LAYER_HEAD_TOKEN) {
-        for (int idx = tid; idx < RPB * p.n_sel; idx += kBlock) {
-            const int r = idx / p.n_sel, a = idx % p.n_sel;
+        for (int idx = tid; idx < RPB * n_sel; idx += kBlock) {
+            const int r = idx / n_sel, a = idx % n_sel;
             const int tt = tile * RPB + r;
             const int64_t slot = p.gran == KVCOMM_W_TOKEN ? tt : 0;
-            w_lds[idx] = tt < p.S ? p.weights[slot * p.w_pitch + p.col[a]] : 0.f;
+            w_lds[idx] = tt < jb.S ? jb.weights[slot * jb.w_pitch + p.col[a0 + a]] : 0.f;
         }
     }
     __syncthreads();
     if (!valid) return;
 
-    const bool rot_base = is_k && p.base_tab != 0;
+    const bool rot_base = is_k && jb.base_tab != 0;
     float bc[EPV], bs[EPV];
     if (rot_base) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            const float2 v = cs[(p.base_tab - 1) * HALF + lir * EPV + e];
+            const float2 v = cs[(jb.base_tab - 1) * HALF + lir * EPV + e];
             bc[e] = v.x;
             bs[e] = v.y;
         }
     }
 
-    const T *bp = static_cast<const T *>(p.base[which]);
-    T *op = static_cast<T *>(p.out[which]);
-    const Strides sb = p.s_base[which], so = p.s_out[which];
+    const T *bp = static_cast<const T *>(jb.base[which]);
+    T *op = static_cast<T *>(jb.out[which]);
+    const Strides sb = jb.s_base[which], so = jb.s_out[which];
     const int64_t col0 = (int64_t)lir * EPV;
 
     for (int lh = lh0; lh < lh1; ++lh) {
@@ -111,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
         const u32x4 rlo = load16_stream(xp), rhi = load16_stream(xp + HALF);
         const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + col0;
         const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN
-                                ? p.weights + ((int64_t)lh * p.S + t) * p.w_pitch
+                                ? jb.weights + ((int64_t)lh * jb.S + t) * jb.w_pitch
                                 : nullptr;
 
         float lo[EPV], hi[EPV];
@@ -127,11 +156,11 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
         }
 
         auto accumulate = [&](int a, const u32x4 &rdlo, const u32x4 &rdhi) {
-            const float w = wrow ? wrow[p.col[a]] : w_lds[row * p.n_sel + a];
+            const float w = wrow ? wrow[p.col[a0 + a]] : w_lds[row * n_sel + a];
             float dlo[EPV], dhi[EPV];
             unpack<T>(rdlo, dlo);
             unpack<T>(rdhi, dhi);
-            const int tb = is_k ? p.tab[a] : 0;
+            const int tb = is_k ? p.tab[a0 + a] : 0;
             if (tb) {
                 const float2 *tcs = cs + (tb - 1) * HALF + lir * EPV;
 #pragma unroll
@@ -149,21 +178,21 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
             }
         };
 
-        // Four anchors (eight independent 16-byte loads) are kept in flight.
+        // kAnchorsInFlight anchors (twice as many independent 16-byte loads) are kept in flight.
         int a = 0;
-        for (; a + 4 <= p.n_sel; a += 4) {
-            u32x4 x[4][2];
+        for (; a + kAnchorsInFlight <= n_sel; a += kAnchorsInFlight) {
+            u32x4 x[kAnchorsInFlight][2];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const T *d = static_cast<const T *>(p.anc[which][a + u]) + aoff;
+            for (int u = 0; u < kAnchorsInFlight; ++u) {
+                const T *d = static_cast<const T *>(p.anc[which][a0 + a + u]) + aoff;
                 x[u][0] = load16_stream(d);
                 x[u][1] = load16_stream(d + HALF);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
+            for (int u = 0; u < kAnchorsInFlight; ++u) accumulate(a + u, x[u][0], x[u][1]);
         }
-        for (; a < p.n_sel; ++a) {
-            const T *d = static_cast<const T *>(p.anc[which][a]) + aoff;
+        for (; a < n_sel; ++a) {
+            const T *d = static_cast<const T *>(p.anc[which][a0 + a]) + aoff;
             const u32x4 x0 = load16_stream(d), x1 = load16_stream(d + HALF);
             accumulate(a, x0, x1);
         }
@@ -175,16 +204,142 @@ __global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
 }
 
 template <typename T, int LPR>
-int launch_align(const AlignParams &p, int n_blocks, hipStream_t stream)
+int launch_align(const AlignParams &p, int n_blocks, int max_tab, int max_sel, hipStream_t stream)
 {
     constexpr int HALF = LPR * Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
-    const size_t lds = sizeof(float2) * (size_t)p.n_tab * HALF + sizeof(float) * (size_t)RPB * p.n_sel;
+    const size_t lds = sizeof(float2) * (size_t)max_tab * HALF + sizeof(float) * (size_t)RPB * max_sel;
     hipLaunchKernelGGL((align_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
     return launch_status();
 }
 
 }  // namespace
+
+extern "C" int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
+                                     const kvcomm_align_job *jobs, int32_t n_jobs, void *stream)
+{
+    int st = check_model(model);
+    if (st) return st;
+    if ((st = check_gran(gran))) return st;
+    if (!jobs || n_jobs <= 0) return KVCOMM_EINVAL;
+    if (n_jobs > KVCOMM_MAX_BATCH) return KVCOMM_EUNSUPPORTED;
+    const int dt = model->dtype;
+    bool any_anchor = false;
+    for (int j = 0; j < n_jobs; ++j) {
+        const kvcomm_align_job &jd = jobs[j];
+        if (jd.seg_len <= 0 || jd.n_anchors < 0) return KVCOMM_EINVAL;
+        if (jd.n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
+        if ((st = check_tensor(jd.base_k, dt, true)) || (st = check_tensor(jd.base_v, dt, true)) ||
+            (st = check_tensor(jd.out_k, dt, true)) || (st = check_tensor(jd.out_v, dt, true)))
+            return st;
+        if (jd.n_anchors > 0) {
+            if (!jd.anchor_dk || !jd.anchor_dv || !jd.anchor_len || !jd.weights) return KVCOMM_EINVAL;
+            any_anchor = true;
+        }
+    }
+    if (any_anchor && (st = check_tensor(anchor_layout, dt, false))) return st;
+
+    AlignParams p{};
+    p.s_anc = strides_of(anchor_layout);
+    p.H = model->n_kv_heads;
+    p.LH = model->n_layers * model->n_kv_heads;
+    p.gran = gran;
+    p.n_jobs = n_jobs;
+    for (int i = 0; i < model->head_dim / 2; ++i)
+        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
+
+    const int es = elem_size(dt);
+    const int lpr = model->head_dim / (2 * (16 / es));
+    const int rpb = kBlock / lpr;
+    int n_tab_total = 0, n_sel_total = 0, max_tab = 0, max_sel = 0;
+    int64_t tiles_total = 0;
+    for (int j = 0; j < n_jobs; ++j) {
+        const kvcomm_align_job &jd = jobs[j];
+        AlignJob &jb = p.job[j];
+        jb.base[0] = jd.base_k.ptr;
+        jb.base[1] = jd.base_v.ptr;
+        jb.out[0] = jd.out_k.ptr;
+        jb.out[1] = jd.out_v.ptr;
+        jb.s_base[0] = strides_of(jd.base_k);
+        jb.s_base[1] = strides_of(jd.base_v);
+        jb.s_out[0] = strides_of(jd.out_k);
+        jb.s_out[1] = strides_of(jd.out_v);
+        jb.weights = jd.weights;
+        jb.S = jd.seg_len;
+        jb.w_pitch = jd.n_anchors;
+        jb.a0 = (int16_t)n_sel_total;
+        jb.t0 = (int16_t)n_tab_total;
+        // Rotation tables of the segment: one per distinct non-zero position delta (base keys: delta_pos;
+        // anchor a's deviation: delta_pos - anchor_delta_pos[a]).
+        int n_tab = 0;
+        bool overflow = false;
+        auto table_of = [&](int32_t d) -> int {
+            if (d == 0) return 0;
+            for (int r = 0; r < n_tab; ++r)
+                if (p.tab_delta[n_tab_total + r] == d) return r + 1;
+            if (n_tab_total + n_tab >= kMaxTab) {
+                overflow = true;
+                return 0;
+            }
+            p.tab_delta[n_tab_total + n_tab] = d;
+            return ++n_tab;
+        };
+        jb.base_tab = (int16_t)table_of(jd.delta_pos);
+        int n_sel = 0;
+        for (int a = 0; a < jd.n_anchors; ++a) {
+            if (jd.anchor_len[a] < 0) return KVCOMM_EINVAL;
+            if (jd.anchor_len[a] < jd.seg_len) continue;  // not selected: never read
+            if (!jd.anchor_dk[a] || !jd.anchor_dv[a] || !aligned16(jd.anchor_dk[a]) || !aligned16(jd.anchor_dv[a]))
+                return KVCOMM_EINVAL;
+            if (n_sel_total + n_sel >= KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;  // over all segments of the launch
+            const int s = n_sel_total + n_sel++;
+            p.anc[0][s] = jd.anchor_dk[a];
+            p.anc[1][s] = jd.anchor_dv[a];
+            p.col[s] = (uint8_t)a;
+            p.tab[s] = (uint8_t)(jd.anchor_delta_pos ? table_of(jd.delta_pos - jd.anchor_delta_pos[a]) : 0);
+        }
+        if (overflow) return KVCOMM_EUNSUPPORTED;
+        jb.n_sel = (int16_t)n_sel;
+        jb.n_tab = (int16_t)n_tab;
+        n_sel_total += n_sel;
+        n_tab_total += n_tab;
+        max_tab = n_tab > max_tab ? n_tab : max_tab;
+        max_sel = n_sel > max_sel ? n_sel : max_sel;
+        jb.n_token_tiles = (jd.seg_len + rpb - 1) / rpb;
+        tiles_total += jb.n_token_tiles;
+    }
+
+    // Many small blocks: the memory system delivers more with more wavefronts in flight, and the
+    // per-block set-up (weights, cos/sin) is a few dozen instructions.
+    const int64_t target_blocks = (int64_t)KVC_ALIGN_BLOCKS * n_jobs;
+    int64_t n_chunks = (target_blocks + tiles_total - 1) / tiles_total;
+    if (n_chunks > p.LH) n_chunks = p.LH;
+    if (n_chunks < 1) n_chunks = 1;
+    p.lh_per_block = (int32_t)((p.LH + n_chunks - 1) / n_chunks);
+    n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
+    int64_t n_blocks = 0;
+    for (int j = 0; j < n_jobs; ++j) {
+        p.job[j].block0 = (int32_t)n_blocks;
+        n_blocks += n_chunks * p.job[j].n_token_tiles;
+    }
+    if (n_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (dt == KVCOMM_BF16) {
+        switch (lpr) {
+            case 4: return launch_align<bf16_t, 4>(p, (int)n_blocks, max_tab, max_sel, s);
+            case 8: return launch_align<bf16_t, 8>(p, (int)n_blocks, max_tab, max_sel, s);
+            case 16: return launch_align<bf16_t, 16>(p, (int)n_blocks, max_tab, max_sel, s);
+        }
+    } else {
+        switch (lpr) {
+            case 8: return launch_align<float, 8>(p, (int)n_blocks, max_tab, max_sel, s);
+            case 16: return launch_align<float, 16>(p, (int)n_blocks, max_tab, max_sel, s);
+            case 32: return launch_align<float, 32>(p, (int)n_blocks, max_tab, max_sel, s);
+        }
+    }
+    return KVCOMM_EUNSUPPORTED;
+}
 
 extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_tensor base_k, kvcomm_tensor base_v,
                                int32_t seg_len, const void *const *anchor_dk, const void *const *anchor_dv,
@@ -192,87 +347,18 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
                                const float *weights, int32_t delta_pos, const int32_t *anchor_delta_pos,
                                kvcomm_tensor out_k, kvcomm_tensor out_v, void *stream)
 {
-    int st = check_model(model);
-    if (st) return st;
-    if ((st = check_gran(gran))) return st;
-    if (seg_len <= 0 || n_anchors < 0) return KVCOMM_EINVAL;
-    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
-    const int dt = model->dtype;
-    if ((st = check_tensor(base_k, dt, true)) || (st = check_tensor(base_v, dt, true)) ||
-        (st = check_tensor(out_k, dt, true)) || (st = check_tensor(out_v, dt, true)))
-        return st;
-    if (n_anchors > 0) {
-        if (!anchor_dk || !anchor_dv || !anchor_len || !weights) return KVCOMM_EINVAL;
-        if ((st = check_tensor(anchor_layout, dt, false))) return st;
-    }
-
-    AlignParams p{};
-    p.base[0] = base_k.ptr;
-    p.base[1] = base_v.ptr;
-    p.out[0] = out_k.ptr;
-    p.out[1] = out_v.ptr;
-    p.s_base[0] = strides_of(base_k);
-    p.s_base[1] = strides_of(base_v);
-    p.s_out[0] = strides_of(out_k);
-    p.s_out[1] = strides_of(out_v);
-    p.s_anc = strides_of(anchor_layout);
-    p.weights = weights;
-    p.H = model->n_kv_heads;
-    p.S = seg_len;
-    p.LH = model->n_layers * model->n_kv_heads;
-    p.w_pitch = n_anchors;
-    p.gran = gran;
-    for (int i = 0; i < model->head_dim / 2; ++i)
-        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
-
-    // Rotation tables: one per distinct non-zero position delta (base keys: delta_pos;
-    // anchor a's deviation: delta_pos - anchor_delta_pos[a]).
-    auto table_of = [&](int32_t d) -> int {
-        if (d == 0) return 0;
-        for (int r = 0; r < p.n_tab; ++r)
-            if (p.tab_delta[r] == d) return r + 1;
-        p.tab_delta[p.n_tab] = d;
-        return ++p.n_tab;
-    };
-    p.base_tab = table_of(delta_pos);
-    for (int a = 0; a < n_anchors; ++a) {
-        if (anchor_len[a] < 0) return KVCOMM_EINVAL;
-        if (anchor_len[a] < seg_len) continue;  // not selected: never read
-        if (!anchor_dk[a] || !anchor_dv[a] || !aligned16(anchor_dk[a]) || !aligned16(anchor_dv[a])) return KVCOMM_EINVAL;
-        const int s = p.n_sel++;
-        p.anc[0][s] = anchor_dk[a];
-        p.anc[1][s] = anchor_dv[a];
-        p.col[s] = (uint8_t)a;
-        p.tab[s] = (uint8_t)(anchor_delta_pos ? table_of(delta_pos - anchor_delta_pos[a]) : 0);
-    }
-
-    const int es = elem_size(dt);
-    const int lpr = model->head_dim / (2 * (16 / es));
-    const int rpb = kBlock / lpr;
-    p.n_token_tiles = (seg_len + rpb - 1) / rpb;
-    // Many small blocks: the memory system delivers more with more wavefronts in flight, and the
-    // per-block set-up (weights, cos/sin) is a few dozen instructions.
-    const int target_blocks = 32768;
-    int n_chunks = (target_blocks + p.n_token_tiles - 1) / p.n_token_tiles;
-    if (n_chunks > p.LH) n_chunks = p.LH;
-    if (n_chunks < 1) n_chunks = 1;
-    p.lh_per_block = (p.LH + n_chunks - 1) / n_chunks;
-    n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
-    const int n_blocks = n_chunks * p.n_token_tiles;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-
-    if (dt == KVCOMM_BF16) {
-        switch (lpr) {
-            case 4: return launch_align<bf16_t, 4>(p, n_blocks, s);
-            case 8: return launch_align<bf16_t, 8>(p, n_blocks, s);
-            case 16: return launch_align<bf16_t, 16>(p, n_blocks, s);
-        }
-    } else {
-        switch (lpr) {
-            case 8: return launch_align<float, 8>(p, n_blocks, s);
-            case 16: return launch_align<float, 16>(p, n_blocks, s);
-            case 32: return launch_align<float, 32>(p, n_blocks, s);
-        }
-    }
-    return KVCOMM_EUNSUPPORTED;
+    kvcomm_align_job job{};
+    job.base_k = base_k;
+    job.base_v = base_v;
+    job.out_k = out_k;
+    job.out_v = out_v;
+    job.seg_len = seg_len;
+    job.delta_pos = delta_pos;
+    job.anchor_dk = anchor_dk;
+    job.anchor_dv = anchor_dv;
+    job.anchor_len = anchor_len;
+    job.anchor_delta_pos = anchor_delta_pos;
+    job.n_anchors = n_anchors;
+    job.weights = weights;
+    return kvcomm_align_kv_batch(model, gran, anchor_layout, &job, 1, stream);
 }

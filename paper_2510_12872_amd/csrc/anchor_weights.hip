@@ -24,45 +24,69 @@ namespace {
 
 using namespace kvc;
 
+#ifndef KVC_DIST_BLOCKS
+#define KVC_DIST_BLOCKS 2048  // blocks the distance grid aims at (measured best on MI355X among 1024 ... 8192)
+#endif
+
 constexpr int kBlock = 256;
 constexpr int kAnchorTile = 16;  // anchors whose accumulators one lane keeps in registers
 
+// How a launch is cut into blocks.  Rows of one (layer, head) are LPR lanes wide; a block owns RPB
+// consecutive tokens and a run of lh_per_block (layer, head) pairs ("chunk").
 struct DistPlan {
     int lpr;            // lanes per row = D / EPV
     int rpb;            // rows (tokens) per block
-    int n_token_tiles;
     int lh_per_block;
     int n_chunks;
 };
 
-DistPlan make_plan(const kvcomm_model *m, int seg_len, int gran)
+// seg_lens: the segments of the launch (one for the single-segment entry points).
+DistPlan make_plan(const kvcomm_model *m, const int32_t *seg_lens, int n_jobs, int gran)
 {
     DistPlan pl;
     const int epv = 16 / elem_size(m->dtype);
     pl.lpr = m->head_dim / epv;
     pl.rpb = kBlock / pl.lpr;
-    pl.n_token_tiles = (seg_len + pl.rpb - 1) / pl.rpb;
     const int LH = m->n_layers * m->n_kv_heads;
     if (gran == KVCOMM_W_LAYER_HEAD_TOKEN) {
         pl.lh_per_block = 1;
     } else {
-        const int target_blocks = 2048;  // measured best on MI355X among 1024 / 2048 / 4096 / 8192
-        int n_chunks = (target_blocks + pl.n_token_tiles - 1) / pl.n_token_tiles;
+        int64_t tiles = 0;
+        for (int j = 0; j < n_jobs; ++j) tiles += (seg_lens[j] + pl.rpb - 1) / pl.rpb;
+        const int64_t target_blocks = (int64_t)KVC_DIST_BLOCKS * n_jobs;
+        int64_t n_chunks = (target_blocks + tiles - 1) / tiles;
         if (n_chunks > LH) n_chunks = LH;
         if (n_chunks < 1) n_chunks = 1;
-        pl.lh_per_block = (LH + n_chunks - 1) / n_chunks;
+        pl.lh_per_block = (int)((LH + n_chunks - 1) / n_chunks);
     }
     pl.n_chunks = (LH + pl.lh_per_block - 1) / pl.lh_per_block;
     return pl;
 }
 
-struct DistParams {
+struct DistJob {
     const void *seg_k;
-    Strides s_seg, s_anc;
-    double *partial;  // [n_chunks][S][n_sel]
-    int32_t H, S, LH, n_sel, lh_per_block, n_token_tiles;
-    const void *anc[KVCOMM_MAX_ANCHORS];  // selected anchors, original order
+    Strides s_seg;
+    double *partial;       // [component][n_chunks][S][n_sel]
+    int64_t comp_stride;   // elements between components (cosine rule)
+    int32_t S, n_token_tiles, block0;
+    int16_t a0, n_sel;     // its selected anchors: entries [a0, a0 + n_sel) of anc
 };
+
+struct DistParams {
+    DistJob job[KVCOMM_MAX_BATCH];
+    Strides s_anc;
+    int32_t H, LH, lh_per_block, n_jobs;
+    const void *anc[KVCOMM_MAX_ANCHORS];  // selected anchors of all segments
+};
+
+__device__ __forceinline__ int job_of_block(const DistParams &p)
+{
+    int ji = 0;
+#pragma unroll
+    for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
+        if (i < p.n_jobs && (int)blockIdx.x >= p.job[i].block0) ji = i;
+    return ji;
+}
 
 // Sum of squared differences of two 16-byte vectors, added to a double accumulator.
 template <typename T>
@@ -82,14 +106,17 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
+    const DistJob &jb = p.job[job_of_block(p)];
     const int tid = threadIdx.x;
     const int row = tid / LPR, lir = tid % LPR;
-    const int tile = blockIdx.x % p.n_token_tiles;
-    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int bx = blockIdx.x - jb.block0;
+    const int tile = bx % jb.n_token_tiles;
+    const int chunk = bx / jb.n_token_tiles;
     const int a0 = blockIdx.y * kAnchorTile;
-    const int na = min(kAnchorTile, p.n_sel - a0);
+    const int na = min(kAnchorTile, jb.n_sel - a0);
+    if (na <= 0) return;  // the grid's anchor tiles cover the largest pool of the launch
     const int t = tile * RPB + row;
-    const bool valid = t < p.S;
+    const bool valid = t < jb.S;
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
@@ -98,15 +125,15 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
     for (int j = 0; j < kAnchorTile; ++j) acc[j] = 0.0;
 
     if (valid) {
-        const T *seg = static_cast<const T *>(p.seg_k);
+        const T *seg = static_cast<const T *>(jb.seg_k);
         for (int lh = lh0; lh < lh1; ++lh) {
             const int l = lh / p.H, h = lh % p.H;
-            const u32x4 rs = load16_stream(seg + l * p.s_seg.layer + h * p.s_seg.head + t * p.s_seg.token + lir * EPV);
+            const u32x4 rs = load16_stream(seg + l * jb.s_seg.layer + h * jb.s_seg.head + t * jb.s_seg.token + lir * EPV);
             const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + lir * EPV;
             u32x4 ra[kAnchorTile];
 #pragma unroll
             for (int j = 0; j < kAnchorTile; ++j)
-                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[a0 + j]) + aoff);
+                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[jb.a0 + a0 + j]) + aoff);
             float x[EPV];
             unpack<T>(rs, x);
 #pragma unroll
@@ -121,7 +148,7 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
             double v = acc[j];
 #pragma unroll
             for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
-            if (valid && lir == 0) p.partial[((int64_t)chunk * p.S + t) * p.n_sel + a0 + j] = v;
+            if (valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
         }
     }
 }
@@ -131,18 +158,21 @@ constexpr int kCosTile = 8;  // anchors per lane in the cosine variant (two accu
 // Cosine variant: per chunk, token and selected anchor the three sums <x,y>, |x|^2, |y|^2
 // (x = segment key row, y = anchor key row), laid out [component][chunk][token][anchor].
 template <typename T, int LPR>
-__global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p, const int64_t comp_stride)
+__global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
+    const DistJob &jb = p.job[job_of_block(p)];
     const int tid = threadIdx.x;
     const int row = tid / LPR, lir = tid % LPR;
-    const int tile = blockIdx.x % p.n_token_tiles;
-    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int bx = blockIdx.x - jb.block0;
+    const int tile = bx % jb.n_token_tiles;
+    const int chunk = bx / jb.n_token_tiles;
     const int a0 = blockIdx.y * kCosTile;
-    const int na = min(kCosTile, p.n_sel - a0);
+    const int na = min(kCosTile, jb.n_sel - a0);
+    if (na <= 0) return;
     const int t = tile * RPB + row;
-    const bool valid = t < p.S;
+    const bool valid = t < jb.S;
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
@@ -151,15 +181,15 @@ __global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p,
     for (int j = 0; j < kCosTile; ++j) dot[j] = ny[j] = 0.0;
 
     if (valid) {
-        const T *seg = static_cast<const T *>(p.seg_k);
+        const T *seg = static_cast<const T *>(jb.seg_k);
         for (int lh = lh0; lh < lh1; ++lh) {
             const int l = lh / p.H, h = lh % p.H;
-            const u32x4 rs = load16_stream(seg + l * p.s_seg.layer + h * p.s_seg.head + t * p.s_seg.token + lir * EPV);
+            const u32x4 rs = load16_stream(seg + l * jb.s_seg.layer + h * jb.s_seg.head + t * jb.s_seg.token + lir * EPV);
             const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + lir * EPV;
             u32x4 ra[kCosTile];
 #pragma unroll
             for (int j = 0; j < kCosTile; ++j)
-                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[a0 + j]) + aoff);
+                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[jb.a0 + a0 + j]) + aoff);
             float x[EPV];
             unpack<T>(rs, x);
 #pragma unroll
@@ -189,25 +219,31 @@ __global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p,
                 v += __shfl_xor(v, off, LPR);
             }
             if (valid && lir == 0) {
-                const int64_t i = ((int64_t)chunk * p.S + t) * p.n_sel + a0 + j;
-                p.partial[i] = u;
-                p.partial[comp_stride + i] = nx;
-                p.partial[2 * comp_stride + i] = v;
+                const int64_t i = ((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j;
+                jb.partial[i] = u;
+                jb.partial[jb.comp_stride + i] = nx;
+                jb.partial[2 * jb.comp_stride + i] = v;
             }
         }
     }
 }
 
-struct FinalParams {
+struct FinalJob {
     const double *partial;
     float *weights;
     int32_t *nearest;
     int32_t *selected_out;
-    int32_t S, n_slots, n_sel, n_anchors, n_chunks, gran, chunk_lanes, rule;
-    int64_t comp_stride;  // cosine rule: elements between the three partial components
+    int64_t comp_stride;   // cosine rule: elements between the three partial components
+    uint64_t sel_mask;     // bit a = anchor a is selected
+    int32_t S, n_slots, n_anchors, chunk_lanes, block0;
+    int16_t a0, n_sel;     // its selected anchors: entries [a0, a0 + n_sel) of col
+};
+
+struct FinalParams {
+    FinalJob job[KVCOMM_MAX_BATCH];
+    int32_t n_chunks, gran, rule, n_jobs;
     double tau;
-    uint8_t col[KVCOMM_MAX_ANCHORS];   // original index of selected anchor
-    uint8_t is_sel[KVCOMM_MAX_ANCHORS];
+    uint8_t col[KVCOMM_MAX_ANCHORS];   // original index of a selected anchor
 };
 
 // Score whose softmax across anchors gives the weights: minus the l2 distance, or the cosine
@@ -222,11 +258,11 @@ __device__ __forceinline__ double score_of(const FinalParams &p, double s0, doub
 // Softmax over the selected anchors of one slot, evaluated identically by each of the
 // slot's threads from the scores in `sc` (LDS): every thread walks the anchors in index
 // order, so all agree bit for bit on the maximum, the arg-max and the denominator.
-__device__ __forceinline__ void slot_softmax(const FinalParams &p, const double *sc, int a, int64_t slot)
+__device__ __forceinline__ void slot_softmax(const FinalParams &p, const FinalJob &jb, const double *sc, int a, int64_t slot)
 {
     double smax = sc[0];
     int best = 0;
-    for (int j = 1; j < p.n_sel; ++j)
+    for (int j = 1; j < jb.n_sel; ++j)
         if (sc[j] > smax) {
             smax = sc[j];
             best = j;
@@ -236,14 +272,14 @@ __device__ __forceinline__ void slot_softmax(const FinalParams &p, const double 
         w = a == best ? 1.0 : 0.0;
     } else {
         double denom = 0.0;
-        for (int j = 0; j < p.n_sel; ++j) denom += exp((sc[j] - smax) / p.tau);
+        for (int j = 0; j < jb.n_sel; ++j) denom += exp((sc[j] - smax) / p.tau);
         w = exp((sc[a] - smax) / p.tau) / denom;
     }
-    p.weights[slot * p.n_anchors + p.col[a]] = (float)w;
+    jb.weights[slot * jb.n_anchors + p.col[jb.a0 + a]] = (float)w;
     if (a == 0) {
-        if (p.nearest) p.nearest[slot] = p.col[best];
-        for (int c = 0; c < p.n_anchors; ++c)
-            if (!p.is_sel[c]) p.weights[slot * p.n_anchors + c] = 0.f;
+        if (jb.nearest) jb.nearest[slot] = p.col[jb.a0 + best];
+        for (int c = 0; c < jb.n_anchors; ++c)
+            if (!((jb.sel_mask >> c) & 1)) jb.weights[slot * jb.n_anchors + c] = 0.f;
     }
 }
 
@@ -253,39 +289,45 @@ __device__ __forceinline__ void slot_softmax(const FinalParams &p, const double 
 __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
 {
     __shared__ double dsh[kBlock];
+    int ji = 0;
+#pragma unroll
+    for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
+        if (i < p.n_jobs && (int)blockIdx.x >= p.job[i].block0) ji = i;
+    const FinalJob &jb = p.job[ji];
+    const int bx = blockIdx.x - jb.block0;
     const int tid = threadIdx.x;
-    if (blockIdx.x == 0 && p.selected_out && tid < p.n_anchors) p.selected_out[tid] = p.is_sel[tid];
-    if (p.n_sel == 0) {  // nothing selected: all weights 0, nearest -1
-        const int64_t slot = (int64_t)blockIdx.x * kBlock + tid;
-        if (slot < p.n_slots) {
-            for (int c = 0; c < p.n_anchors; ++c) p.weights[slot * p.n_anchors + c] = 0.f;
-            if (p.nearest) p.nearest[slot] = -1;
+    if (bx == 0 && jb.selected_out && tid < jb.n_anchors) jb.selected_out[tid] = (int32_t)((jb.sel_mask >> tid) & 1);
+    if (jb.n_sel == 0) {  // nothing selected: all weights 0, nearest -1
+        const int64_t slot = (int64_t)bx * kBlock + tid;
+        if (slot < jb.n_slots) {
+            for (int c = 0; c < jb.n_anchors; ++c) jb.weights[slot * jb.n_anchors + c] = 0.f;
+            if (jb.nearest) jb.nearest[slot] = -1;
         }
         return;
     }
-    const int CL = p.chunk_lanes;          // power of two, CL * n_sel <= kBlock
-    const int spb = kBlock / (CL * p.n_sel);  // slots per block
-    const int cl = tid % CL, a = (tid / CL) % p.n_sel, sl = tid / (CL * p.n_sel);
-    const int64_t slot = (int64_t)blockIdx.x * spb + sl;
-    const bool active = sl < spb && slot < p.n_slots;
+    const int CL = jb.chunk_lanes;             // power of two, CL * n_sel <= kBlock
+    const int spb = kBlock / (CL * jb.n_sel);  // slots per block
+    const int cl = tid % CL, a = (tid / CL) % jb.n_sel, sl = tid / (CL * jb.n_sel);
+    const int64_t slot = (int64_t)bx * spb + sl;
+    const bool active = sl < spb && slot < jb.n_slots;
     const bool cosine = p.rule == KVCOMM_RULE_COSINE_SOFTMAX;
     double s0 = 0.0, s1 = 0.0, s2 = 0.0;
     if (active) {
         if (p.gran == KVCOMM_W_TOKEN) {
             for (int c = cl; c < p.n_chunks; c += CL) {
-                const int64_t i = ((int64_t)c * p.S + slot) * p.n_sel + a;
-                s0 += p.partial[i];
+                const int64_t i = ((int64_t)c * jb.S + slot) * jb.n_sel + a;
+                s0 += jb.partial[i];
                 if (cosine) {
-                    s1 += p.partial[p.comp_stride + i];
-                    s2 += p.partial[2 * p.comp_stride + i];
+                    s1 += jb.partial[jb.comp_stride + i];
+                    s2 += jb.partial[2 * jb.comp_stride + i];
                 }
             }
         } else if (cl == 0) {
-            const int64_t i = slot * p.n_sel + a;  // one chunk per (layer, head): slot = chunk * S + t
-            s0 = p.partial[i];
+            const int64_t i = slot * jb.n_sel + a;  // one chunk per (layer, head): slot = chunk * S + t
+            s0 = jb.partial[i];
             if (cosine) {
-                s1 = p.partial[p.comp_stride + i];
-                s2 = p.partial[2 * p.comp_stride + i];
+                s1 = jb.partial[jb.comp_stride + i];
+                s2 = jb.partial[2 * jb.comp_stride + i];
             }
         }
     }
@@ -296,31 +338,32 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
             s2 += __shfl_xor(s2, off);
         }
     }
-    if (active && cl == 0) dsh[sl * p.n_sel + a] = score_of(p, s0, s1, s2);
+    if (active && cl == 0) dsh[sl * jb.n_sel + a] = score_of(p, s0, s1, s2);
     __syncthreads();
-    if (active && cl == 0) slot_softmax(p, dsh + sl * p.n_sel, a, slot);
+    if (active && cl == 0) slot_softmax(p, jb, dsh + sl * jb.n_sel, a, slot);
 }
 
-// Per-segment granularity: one block; each selected anchor's partials are added by the 256
+// Per-segment granularity: one block per segment; each selected anchor's partials are added by the 256
 // threads in a fixed strided order and then by a fixed LDS tree.
 __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalParams p)
 {
     __shared__ double red[kBlock];
     __shared__ double dsh[KVCOMM_MAX_ANCHORS];
+    const FinalJob &jb = p.job[blockIdx.x];
     const int tid = threadIdx.x;
-    if (p.selected_out && tid < p.n_anchors) p.selected_out[tid] = p.is_sel[tid];
-    if (p.n_sel == 0) {
-        if (tid < p.n_anchors) p.weights[tid] = 0.f;
-        if (tid == 0 && p.nearest) p.nearest[0] = -1;
+    if (jb.selected_out && tid < jb.n_anchors) jb.selected_out[tid] = (int32_t)((jb.sel_mask >> tid) & 1);
+    if (jb.n_sel == 0) {
+        if (tid < jb.n_anchors) jb.weights[tid] = 0.f;
+        if (tid == 0 && jb.nearest) jb.nearest[0] = -1;
         return;
     }
-    const int64_t n = (int64_t)p.n_chunks * p.S;
+    const int64_t n = (int64_t)p.n_chunks * jb.S;
     const int n_comp = p.rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
-    for (int a = 0; a < p.n_sel; ++a) {
+    for (int a = 0; a < jb.n_sel; ++a) {
         double tot[3] = {0.0, 0.0, 0.0};
         for (int c = 0; c < n_comp; ++c) {
             double s = 0.0;
-            for (int64_t i = tid; i < n; i += kBlock) s += p.partial[c * p.comp_stride + i * p.n_sel + a];
+            for (int64_t i = tid; i < n; i += kBlock) s += jb.partial[c * jb.comp_stride + i * jb.n_sel + a];
             red[tid] = s;
             __syncthreads();
             for (int off = kBlock / 2; off >= 1; off >>= 1) {
@@ -333,17 +376,17 @@ __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalPar
         if (tid == 0) dsh[a] = score_of(p, tot[0], tot[1], tot[2]);
     }
     __syncthreads();
-    if (tid < p.n_sel) slot_softmax(p, dsh, tid, 0);
+    if (tid < jb.n_sel) slot_softmax(p, jb, dsh, tid, 0);
 }
 
 template <typename T, int LPR>
-int launch_dist(const DistParams &p, int n_blocks, bool cosine, int64_t comp_stride, hipStream_t stream)
+int launch_dist(const DistParams &p, int n_blocks, int max_sel, bool cosine, hipStream_t stream)
 {
     if (cosine) {
-        const int a_tiles = (p.n_sel + kCosTile - 1) / kCosTile;
-        hipLaunchKernelGGL((cos_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p, comp_stride);
+        const int a_tiles = (max_sel + kCosTile - 1) / kCosTile;
+        hipLaunchKernelGGL((cos_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
     } else {
-        const int a_tiles = (p.n_sel + kAnchorTile - 1) / kAnchorTile;
+        const int a_tiles = (max_sel + kAnchorTile - 1) / kAnchorTile;
         hipLaunchKernelGGL((dist_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
     }
     return launch_status();
@@ -356,6 +399,15 @@ int check_rule(int rule)
                : KVCOMM_EINVAL;
 }
 
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Bytes of segment j's partial sums for a plan.
+size_t job_partial_bytes(const DistPlan &pl, int32_t seg_len, int32_t n_anchors, int rule)
+{
+    const size_t n_comp = rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
+    return sizeof(double) * n_comp * (size_t)pl.n_chunks * seg_len * n_anchors;
+}
+
 }  // namespace
 
 extern "C" size_t kvcomm_weight_slots(const kvcomm_model *model, int32_t seg_len, int32_t gran)
@@ -366,21 +418,157 @@ extern "C" size_t kvcomm_weight_slots(const kvcomm_model *model, int32_t seg_len
     return (size_t)model->n_layers * model->n_kv_heads * seg_len;
 }
 
+extern "C" size_t kvcomm_anchor_weights_batch_workspace(const kvcomm_model *model, int32_t gran, int32_t rule,
+                                                        const int32_t *seg_lens, const int32_t *n_anchors,
+                                                        int32_t n_jobs)
+{
+    if (check_model(model) || check_gran(gran) || check_rule(rule) || !seg_lens || !n_anchors || n_jobs <= 0 ||
+        n_jobs > KVCOMM_MAX_BATCH)
+        return 0;
+    for (int j = 0; j < n_jobs; ++j)
+        if (seg_lens[j] <= 0 || n_anchors[j] <= 0 || n_anchors[j] > KVCOMM_MAX_ANCHORS) return 0;
+    const DistPlan pl = make_plan(model, seg_lens, n_jobs, gran);
+    size_t total = 0;
+    for (int j = 0; j < n_jobs; ++j) total += align256(job_partial_bytes(pl, seg_lens[j], n_anchors[j], rule));
+    return total;
+}
+
 extern "C" size_t kvcomm_anchor_weights_rule_workspace(const kvcomm_model *model, int32_t seg_len, int32_t n_anchors,
                                                        int32_t gran, int32_t rule)
 {
     if (check_model(model) || check_gran(gran) || check_rule(rule) || seg_len <= 0 || n_anchors <= 0 ||
         n_anchors > KVCOMM_MAX_ANCHORS)
         return 0;
-    const DistPlan pl = make_plan(model, seg_len, gran);
-    const size_t n_comp = rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
-    return sizeof(double) * n_comp * (size_t)pl.n_chunks * seg_len * n_anchors;
+    const DistPlan pl = make_plan(model, &seg_len, 1, gran);
+    return job_partial_bytes(pl, seg_len, n_anchors, rule);
 }
 
 extern "C" size_t kvcomm_anchor_weights_workspace(const kvcomm_model *model, int32_t seg_len, int32_t n_anchors,
                                                   int32_t gran)
 {
     return kvcomm_anchor_weights_rule_workspace(model, seg_len, n_anchors, gran, KVCOMM_RULE_L2_SOFTMAX);
+}
+
+extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,
+                                           kvcomm_tensor anchor_layout, const kvcomm_weights_job *jobs,
+                                           int32_t n_jobs, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int st = check_model(model);
+    if (st) return st;
+    if ((st = check_gran(gran)) || (st = check_rule(rule))) return st;
+    if (!jobs || n_jobs <= 0) return KVCOMM_EINVAL;
+    if (n_jobs > KVCOMM_MAX_BATCH) return KVCOMM_EUNSUPPORTED;
+    if (!(temperature > 0.f)) return KVCOMM_EINVAL;  // also rejects NaN
+    const int dt = model->dtype;
+    if ((st = check_tensor(anchor_layout, dt, false))) return st;
+    int32_t seg_lens[KVCOMM_MAX_BATCH];
+    for (int j = 0; j < n_jobs; ++j) {
+        const kvcomm_weights_job &jd = jobs[j];
+        if (jd.seg_len <= 0 || jd.n_anchors <= 0) return KVCOMM_EINVAL;
+        if (jd.n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
+        if ((st = check_tensor(jd.seg_base_k, dt, true))) return st;
+        if (!jd.anchor_base_k || !jd.anchor_len || !jd.weights_out) return KVCOMM_EINVAL;
+        seg_lens[j] = jd.seg_len;
+    }
+
+    const DistPlan pl = make_plan(model, seg_lens, n_jobs, gran);
+    const bool cosine = rule == KVCOMM_RULE_COSINE_SOFTMAX;
+    DistParams dp{};
+    FinalParams fp{};
+    int n_sel_total = 0, max_sel = 0;
+    size_t need = 0;
+    for (int j = 0; j < n_jobs; ++j) {
+        const kvcomm_weights_job &jd = jobs[j];
+        DistJob &dj = dp.job[j];
+        FinalJob &fj = fp.job[j];
+        dj.a0 = fj.a0 = (int16_t)n_sel_total;
+        int n_sel = 0;
+        for (int a = 0; a < jd.n_anchors; ++a) {
+            if (jd.anchor_len[a] < 0) return KVCOMM_EINVAL;
+            if (jd.anchor_len[a] < jd.seg_len) continue;
+            if (!jd.anchor_base_k[a] || !aligned16(jd.anchor_base_k[a])) return KVCOMM_EINVAL;
+            if (n_sel_total + n_sel >= KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;  // over all segments of the launch
+            fp.col[n_sel_total + n_sel] = (uint8_t)a;
+            fj.sel_mask |= (uint64_t)1 << a;
+            dp.anc[n_sel_total + n_sel] = jd.anchor_base_k[a];
+            ++n_sel;
+        }
+        dj.n_sel = fj.n_sel = (int16_t)n_sel;
+        n_sel_total += n_sel;
+        max_sel = n_sel > max_sel ? n_sel : max_sel;
+        need += n_jobs == 1 ? job_partial_bytes(pl, jd.seg_len, jd.n_anchors, rule)
+                            : align256(job_partial_bytes(pl, jd.seg_len, jd.n_anchors, rule));
+    }
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return KVCOMM_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dp.s_anc = strides_of(anchor_layout);
+    dp.H = model->n_kv_heads;
+    dp.LH = model->n_layers * model->n_kv_heads;
+    dp.lh_per_block = pl.lh_per_block;
+    dp.n_jobs = n_jobs;
+    fp.n_chunks = pl.n_chunks;
+    fp.gran = gran;
+    fp.rule = rule;
+    fp.n_jobs = n_jobs;
+    fp.tau = (double)temperature;
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    int64_t dist_blocks = 0, final_blocks = 0;
+    for (int j = 0; j < n_jobs; ++j) {
+        const kvcomm_weights_job &jd = jobs[j];
+        DistJob &dj = dp.job[j];
+        FinalJob &fj = fp.job[j];
+        dj.seg_k = jd.seg_base_k.ptr;
+        dj.s_seg = strides_of(jd.seg_base_k);
+        dj.partial = reinterpret_cast<double *>(ws);
+        ws += align256(job_partial_bytes(pl, jd.seg_len, jd.n_anchors, rule));
+        dj.comp_stride = (int64_t)pl.n_chunks * jd.seg_len * dj.n_sel;  // <= a third of the segment's partials
+        dj.S = jd.seg_len;
+        dj.n_token_tiles = (jd.seg_len + pl.rpb - 1) / pl.rpb;
+        dj.block0 = (int32_t)dist_blocks;
+        dist_blocks += (int64_t)pl.n_chunks * dj.n_token_tiles;
+
+        fj.partial = dj.partial;
+        fj.weights = jd.weights_out;
+        fj.nearest = jd.nearest_out;
+        fj.selected_out = jd.selected_out;
+        fj.comp_stride = dj.comp_stride;
+        fj.S = jd.seg_len;
+        fj.n_slots = (int32_t)kvcomm_weight_slots(model, jd.seg_len, gran);
+        fj.n_anchors = jd.n_anchors;
+        int cl = 1;
+        if (gran == KVCOMM_W_TOKEN && dj.n_sel > 0)
+            while (cl < 8 && 2 * cl * dj.n_sel <= kBlock && 2 * cl <= pl.n_chunks) cl *= 2;
+        fj.chunk_lanes = cl;
+        const int spb = dj.n_sel > 0 ? kBlock / (cl * dj.n_sel) : kBlock;
+        fj.block0 = (int32_t)final_blocks;
+        final_blocks += (fj.n_slots + spb - 1) / spb;
+    }
+    if (dist_blocks > 0x7fffffff || final_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
+
+    if (max_sel > 0) {
+        st = KVCOMM_EUNSUPPORTED;
+        const int nb = (int)dist_blocks;
+        if (dt == KVCOMM_BF16) {
+            switch (pl.lpr) {
+                case 8: st = launch_dist<bf16_t, 8>(dp, nb, max_sel, cosine, s); break;
+                case 16: st = launch_dist<bf16_t, 16>(dp, nb, max_sel, cosine, s); break;
+                case 32: st = launch_dist<bf16_t, 32>(dp, nb, max_sel, cosine, s); break;
+            }
+        } else {
+            switch (pl.lpr) {
+                case 16: st = launch_dist<float, 16>(dp, nb, max_sel, cosine, s); break;
+                case 32: st = launch_dist<float, 32>(dp, nb, max_sel, cosine, s); break;
+                case 64: st = launch_dist<float, 64>(dp, nb, max_sel, cosine, s); break;
+            }
+        }
+        if (st) return st;
+    }
+    if (gran == KVCOMM_W_SEGMENT)
+        hipLaunchKernelGGL(finalize_segment_kernel, dim3(n_jobs), dim3(kBlock), 0, s, fp);
+    else
+        hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)final_blocks), dim3(kBlock), 0, s, fp);
+    return launch_status();
 }
 
 extern "C" int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,
@@ -390,87 +578,17 @@ extern "C" int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gra
                                           int32_t *nearest_out, int32_t *selected_out, void *workspace,
                                           size_t workspace_bytes, void *stream)
 {
-    int st = check_model(model);
-    if (st) return st;
-    if ((st = check_gran(gran)) || (st = check_rule(rule))) return st;
-    if (seg_len <= 0 || n_anchors <= 0) return KVCOMM_EINVAL;
-    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
-    if (!(temperature > 0.f)) return KVCOMM_EINVAL;  // also rejects NaN
-    const int dt = model->dtype;
-    if ((st = check_tensor(seg_base_k, dt, true)) || (st = check_tensor(anchor_layout, dt, false))) return st;
-    if (!anchor_base_k || !anchor_len || !weights_out) return KVCOMM_EINVAL;
-
-    const DistPlan pl = make_plan(model, seg_len, gran);
-    DistParams dp{};
-    FinalParams fp{};
-    for (int a = 0; a < n_anchors; ++a) {
-        if (anchor_len[a] < 0) return KVCOMM_EINVAL;
-        if (anchor_len[a] < seg_len) continue;
-        if (!anchor_base_k[a] || !aligned16(anchor_base_k[a])) return KVCOMM_EINVAL;
-        fp.col[dp.n_sel] = (uint8_t)a;
-        fp.is_sel[a] = 1;
-        dp.anc[dp.n_sel++] = anchor_base_k[a];
-    }
-    const bool cosine = rule == KVCOMM_RULE_COSINE_SOFTMAX;
-    const size_t need = sizeof(double) * (cosine ? 3 : 1) * (size_t)pl.n_chunks * seg_len * n_anchors;
-    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return KVCOMM_EWORKSPACE;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    dp.seg_k = seg_base_k.ptr;
-    dp.s_seg = strides_of(seg_base_k);
-    dp.s_anc = strides_of(anchor_layout);
-    dp.partial = static_cast<double *>(workspace);
-    dp.H = model->n_kv_heads;
-    dp.S = seg_len;
-    dp.LH = model->n_layers * model->n_kv_heads;
-    dp.lh_per_block = pl.lh_per_block;
-    dp.n_token_tiles = pl.n_token_tiles;
-    const int64_t comp_stride = (int64_t)pl.n_chunks * seg_len * dp.n_sel;  // <= a third of the workspace
-
-    if (dp.n_sel > 0) {
-        const int n_blocks = pl.n_chunks * pl.n_token_tiles;
-        st = KVCOMM_EUNSUPPORTED;
-        if (dt == KVCOMM_BF16) {
-            switch (pl.lpr) {
-                case 8: st = launch_dist<bf16_t, 8>(dp, n_blocks, cosine, comp_stride, s); break;
-                case 16: st = launch_dist<bf16_t, 16>(dp, n_blocks, cosine, comp_stride, s); break;
-                case 32: st = launch_dist<bf16_t, 32>(dp, n_blocks, cosine, comp_stride, s); break;
-            }
-        } else {
-            switch (pl.lpr) {
-                case 16: st = launch_dist<float, 16>(dp, n_blocks, cosine, comp_stride, s); break;
-                case 32: st = launch_dist<float, 32>(dp, n_blocks, cosine, comp_stride, s); break;
-                case 64: st = launch_dist<float, 64>(dp, n_blocks, cosine, comp_stride, s); break;
-            }
-        }
-        if (st) return st;
-    }
-
-    fp.partial = dp.partial;
-    fp.weights = weights_out;
-    fp.nearest = nearest_out;
-    fp.selected_out = selected_out;
-    fp.S = seg_len;
-    fp.n_slots = (int32_t)kvcomm_weight_slots(model, seg_len, gran);
-    fp.n_sel = dp.n_sel;
-    fp.n_anchors = n_anchors;
-    fp.n_chunks = pl.n_chunks;
-    fp.gran = gran;
-    fp.rule = rule;
-    fp.comp_stride = comp_stride;
-    fp.tau = (double)temperature;
-    if (gran == KVCOMM_W_SEGMENT) {
-        hipLaunchKernelGGL(finalize_segment_kernel, dim3(1), dim3(kBlock), 0, s, fp);
-    } else {
-        int cl = 1;
-        if (gran == KVCOMM_W_TOKEN && dp.n_sel > 0)
-            while (cl < 8 && 2 * cl * dp.n_sel <= kBlock && 2 * cl <= pl.n_chunks) cl *= 2;
-        fp.chunk_lanes = cl;
-        const int spb = dp.n_sel > 0 ? kBlock / (cl * dp.n_sel) : kBlock;
-        const int n_blocks = (fp.n_slots + spb - 1) / spb;
-        hipLaunchKernelGGL(finalize_kernel, dim3(n_blocks), dim3(kBlock), 0, s, fp);
-    }
-    return launch_status();
+    kvcomm_weights_job job{};
+    job.seg_base_k = seg_base_k;
+    job.seg_len = seg_len;
+    job.anchor_base_k = anchor_base_k;
+    job.anchor_len = anchor_len;
+    job.n_anchors = n_anchors;
+    job.weights_out = weights_out;
+    job.nearest_out = nearest_out;
+    job.selected_out = selected_out;
+    return kvcomm_anchor_weights_batch(model, gran, rule, temperature, anchor_layout, &job, 1, workspace,
+                                       workspace_bytes, stream);
 }
 
 extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float temperature,

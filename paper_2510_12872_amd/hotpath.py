@@ -37,6 +37,44 @@ def align_segment(model, seg, out_k, out_v, temperature=1.0, gran=kv.W_TOKEN, sc
     return scratch
 
 
+class AgentScratch:
+    """Reusable device buffers for the batched weight step of all segments of one agent."""
+
+    def __init__(self, model, seg_lens, n_anchors, gran, device, rule=kv.RULE_L2_SOFTMAX):
+        self.weights, self.nearest, self.selected = [], [], []
+        for S, A in zip(seg_lens, n_anchors):
+            n = kv.kvcomm_weight_slots(model, S, gran)
+            self.weights.append(torch.empty((n, A), dtype=torch.float32, device=device))
+            self.nearest.append(torch.empty((n,), dtype=torch.int32, device=device))
+            self.selected.append(torch.empty((A,), dtype=torch.int32, device=device))
+        need = kv.kvcomm_anchor_weights_batch_workspace(model, seg_lens, n_anchors, gran, rule)
+        self.workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=device)
+
+
+def align_agent_batched(w, model, agent, gran=kv.W_TOKEN, scratch=None, stream=None):
+    """Anchor weights, then aligned K/V of ALL segments of an agent: one batched call per step
+    (chunks of binding.MAX_BATCH segments)."""
+    segs = agent.segments
+    if scratch is None:
+        scratch = AgentScratch(model, [s.base_k.shape[2] for s in segs], [len(s.anchor_k) for s in segs], gran,
+                               segs[0].base_k.device)
+    for c0 in range(0, len(segs), kv.MAX_BATCH):
+        idx = range(c0, min(c0 + kv.MAX_BATCH, len(segs)))
+        kv.kvcomm_anchor_weights_batch(model, [dict(
+            seg_base_k=segs[j].base_k, anchor_base_k=segs[j].anchor_k, anchor_len=segs[j].anchor_len,
+            weights_out=scratch.weights[j], nearest_out=scratch.nearest[j], selected_out=scratch.selected[j])
+            for j in idx], w.temperature, gran, workspace=scratch.workspace, stream=stream)
+        jobs = []
+        for j in idx:
+            p0, S = w.seg_offset(j), segs[j].base_k.shape[2]
+            jobs.append(dict(base_k=segs[j].base_k, base_v=segs[j].base_v, anchor_dk=segs[j].anchor_dk,
+                             anchor_dv=segs[j].anchor_dv, anchor_len=segs[j].anchor_len, weights=scratch.weights[j],
+                             delta_pos=segs[j].delta_pos, anchor_delta_pos=segs[j].anchor_delta_pos,
+                             out_k=agent.cache_k[:, :, p0:p0 + S], out_v=agent.cache_v[:, :, p0:p0 + S]))
+        kv.kvcomm_align_kv_batch(model, jobs, gran, stream)
+    return scratch
+
+
 def reuse_agent(w, model, agent, out=None, gran=kv.W_TOKEN, scratches=None, stream=None):
     """Whole hot path for one agent: align every segment into its cache slot, then suffix attention."""
     for j, seg in enumerate(agent.segments):

@@ -160,6 +160,49 @@ def test_rule_predict_capture_argument_errors(lib):
                                       None) == EINVAL
 
 
+def test_batch_argument_errors(lib):
+    m = _model()
+    parr = (ctypes.c_void_p * 40)(*[0x2000 + 0x100 * i for i in range(40)])
+    larr = (ctypes.c_int32 * 40)(*[16] * 40)
+
+    def ajob(n_anchors=2, seg_len=16, weights=0x4000):
+        return binding._CAlignJob(_tensor(), _tensor(0x5000), _tensor(0x6000), _tensor(0x7000), seg_len, 64, parr, parr,
+                                  larr, None, n_anchors, weights)
+
+    def acall(jobs):
+        arr = (binding._CAlignJob * max(len(jobs), 1))(*jobs)
+        return lib.kvcomm_align_kv_batch(ctypes.byref(m), 0, _tensor(None), arr, len(jobs), None)
+
+    assert acall([]) == EINVAL
+    assert acall([ajob()] * 9) == EUNSUPPORTED                     # more than KVCOMM_MAX_BATCH jobs
+    assert acall([ajob(), ajob(seg_len=0)]) == EINVAL
+    assert acall([ajob(), ajob(weights=None)]) == EINVAL
+    assert acall([ajob(n_anchors=40), ajob(n_anchors=40)]) == EUNSUPPORTED   # 80 selected anchors in one launch
+    assert lib.kvcomm_align_kv_batch(ctypes.byref(m), 0, _tensor(None), None, 1, None) == EINVAL
+
+    def wjob(n_anchors=2, seg_len=16, weights=0x4000):
+        return binding._CWeightsJob(_tensor(), seg_len, parr, larr, n_anchors, weights, None, None)
+
+    def wcall(jobs, ws=0x10000, ws_bytes=1 << 30, tau=1.0):
+        arr = (binding._CWeightsJob * max(len(jobs), 1))(*jobs)
+        return lib.kvcomm_anchor_weights_batch(ctypes.byref(m), 0, 0, tau, _tensor(None), arr, len(jobs), ws, ws_bytes,
+                                               None)
+
+    assert wcall([]) == EINVAL
+    assert wcall([wjob()] * 9) == EUNSUPPORTED
+    assert wcall([wjob(), wjob(weights=None)]) == EINVAL
+    assert wcall([wjob(n_anchors=40), wjob(n_anchors=40)]) == EUNSUPPORTED
+    assert wcall([wjob(), wjob()], tau=0.0) == EINVAL
+    sl = (ctypes.c_int32 * 2)(16, 100)
+    na = (ctypes.c_int32 * 2)(2, 5)
+    need = lib.kvcomm_anchor_weights_batch_workspace(ctypes.byref(m), 0, 0, sl, na, 2)
+    assert need > 0 and need % 256 == 0
+    assert wcall([wjob(), wjob(n_anchors=5, seg_len=100)], ws_bytes=need - 1) == EWORKSPACE
+    assert wcall([wjob(), wjob()], ws=None) == EWORKSPACE
+    assert lib.kvcomm_anchor_weights_batch_workspace(ctypes.byref(m), 0, 0, sl, na, 9) == 0
+    assert lib.kvcomm_anchor_weights_batch_workspace(ctypes.byref(m), 0, 0, sl, None, 2) == 0
+
+
 def _align(lib, m, gran=0, seg_len=16, ptrs=(0x2000,), lens=(16,), weights=0x4000, bk=None, out=None, adp=None):
     A = len(ptrs)
     parr = (ctypes.c_void_p * max(A, 1))(*ptrs)

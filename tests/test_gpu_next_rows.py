@@ -242,3 +242,88 @@ def test_capture_then_align_reproduces_real_cache_fp32():
     kv.kvcomm_align_kv(model, seg.base_k, seg.base_v, [dk], [dv], ones, 777, ok, ov)
     torch.cuda.synchronize()
     assert float((ok - real_k).abs().max()) < 1e-5 and float((ov - real_v).abs().max()) < 1e-6
+
+
+# ------------------------------------------------------------------------- batched launches
+def test_batched_agent_equals_per_segment_calls():
+    """All segments of an agent in one launch per step: K^/V^ bit-identical to per-segment calls
+    (same arithmetic in the same order); weights equal up to the cut of the double partial sums."""
+    w = scaled(workloads.LLAMA8B_5AGENTS, name="batch", n_layers=3, n_kv_heads=2, n_q_heads=8, n_agents=1,
+               prefix_len=16, seg_len=97, n_segments=4, n_anchors=5, tq=8, anchor_delta_choices=(16, 64, 100))
+    say("batched agent")
+    model = hotpath.model_of(w)
+    agent = workloads.make_agent(w, 0, DEV)
+    agent.segments[2].anchor_len[1] = 10          # one unselected anchor in one pool
+    ref_k, ref_v = agent.cache_k.clone(), agent.cache_v.clone()
+    singles = []
+    for j, seg in enumerate(agent.segments):
+        p0 = w.seg_offset(j)
+        singles.append(hotpath.align_segment(model, seg, ref_k[:, :, p0:p0 + w.seg_len], ref_v[:, :, p0:p0 + w.seg_len]))
+    sc = hotpath.align_agent_batched(w, model, agent)
+    torch.cuda.synchronize()
+    for j in range(w.n_segments):
+        assert torch.equal(sc.selected[j], singles[j].selected)
+        assert torch.equal(sc.nearest[j], singles[j].nearest)
+        assert float((sc.weights[j] - singles[j].weights).abs().max()) < 1e-6
+    # same weights in -> bit-identical caches: rerun the batched align with the single-call weights
+    jobs = []
+    for j, seg in enumerate(agent.segments):
+        p0 = w.seg_offset(j)
+        jobs.append(dict(base_k=seg.base_k, base_v=seg.base_v, anchor_dk=seg.anchor_dk, anchor_dv=seg.anchor_dv,
+                         anchor_len=seg.anchor_len, weights=singles[j].weights, delta_pos=seg.delta_pos,
+                         anchor_delta_pos=seg.anchor_delta_pos, out_k=agent.cache_k[:, :, p0:p0 + w.seg_len],
+                         out_v=agent.cache_v[:, :, p0:p0 + w.seg_len]))
+    kv.kvcomm_align_kv_batch(model, jobs)
+    torch.cuda.synchronize()
+    assert torch.equal(agent.cache_k, ref_k) and torch.equal(agent.cache_v, ref_v)
+    # and against the oracle for one of the segments
+    seg = agent.segments[2]
+    bk, anc = oracle_inputs(seg)
+    ref = oracle.reuse_step(bk, to_np(seg.base_v), anc,
+                            [to_np(a) if n >= w.seg_len else np.zeros(bk.shape[:2] + (0, bk.shape[3]))
+                             for a, n in zip(seg.anchor_dk, seg.anchor_len)],
+                            [to_np(a) if n >= w.seg_len else np.zeros(bk.shape[:2] + (0, bk.shape[3]))
+                             for a, n in zip(seg.anchor_dv, seg.anchor_len)],
+                            seg.delta_pos, w.rope_theta, anc_delta=seg.anchor_delta_pos)
+    p0 = w.seg_offset(2)
+    check_weights(sc.weights[2].cpu().numpy(), ref["w"].T)
+    check_close(to_np(agent.cache_k[:, :, p0:p0 + w.seg_len]), ref["out_k"], w.dtype, "K^ batched")
+    check_close(to_np(agent.cache_v[:, :, p0:p0 + w.seg_len]), ref["out_v"], w.dtype, "V^ batched")
+
+
+def test_batched_mixed_lengths_and_prefix_segment_update():
+    """Jobs of different lengths and pool sizes; a prefix-segment job (Eq. "pf_update") that uses the
+    placeholder's per-segment weights with its own tensors."""
+    # all pools are padded to one capacity (77 tokens): the anchors of a launch share one layout
+    w = scaled(SMALL_F32, n_anchors=3, seg_len=40, anchor_lens=(77, 77, 77))
+    say("batched mixed")
+    model = hotpath.model_of(w)
+    ph = workloads.make_segment(w, 0, 0, DEV)                                   # placeholder
+    pf = workloads.make_segment(scaled(w, seg_len=23, seed=5), 0, 1, DEV)       # following prefix segment, other length
+    other = workloads.make_segment(scaled(w, seg_len=77, n_anchors=6, seed=9, anchor_lens=(77,) * 6), 0, 2, DEV)
+    outs = kv.kvcomm_anchor_weights_batch(model, [dict(seg_base_k=ph.base_k, anchor_base_k=ph.anchor_k),
+                                                   dict(seg_base_k=other.base_k, anchor_base_k=other.anchor_k)],
+                                          gran=kv.W_SEGMENT)
+    w_ph, w_other = outs[0][0], outs[1][0]
+    mk = lambda s: (torch.empty_like(s.base_k), torch.empty_like(s.base_v))
+    o_ph, o_pf, o_other = mk(ph), mk(pf), mk(other)
+    kv.kvcomm_align_kv_batch(model, [
+        dict(base_k=ph.base_k, base_v=ph.base_v, anchor_dk=ph.anchor_dk, anchor_dv=ph.anchor_dv, weights=w_ph,
+             delta_pos=64, out_k=o_ph[0], out_v=o_ph[1]),
+        dict(base_k=pf.base_k, base_v=pf.base_v, anchor_dk=pf.anchor_dk, anchor_dv=pf.anchor_dv, weights=w_ph,
+             delta_pos=104, out_k=o_pf[0], out_v=o_pf[1]),
+        dict(base_k=other.base_k, base_v=other.base_v, anchor_dk=other.anchor_dk, anchor_dv=other.anchor_dv,
+             weights=w_other, delta_pos=0, out_k=o_other[0], out_v=o_other[1])], gran=kv.W_SEGMENT)
+    torch.cuda.synchronize()
+    f = to_np
+    d_ph, s_ph = oracle.distances(f(ph.base_k), [f(a) for a in ph.anchor_k], oracle.GRAN_SEGMENT)
+    wo_ph, _ = oracle.weights(d_ph, s_ph, 1.0)
+    d_o, s_o = oracle.distances(f(other.base_k), [f(a) for a in other.anchor_k], oracle.GRAN_SEGMENT)
+    wo_o, _ = oracle.weights(d_o, s_o, 1.0)
+    check_weights(w_ph.cpu().numpy(), wo_ph.T)
+    check_weights(w_other.cpu().numpy(), wo_o.T)
+    for seg, out, wo, delta in ((ph, o_ph, wo_ph, 64), (pf, o_pf, wo_ph, 104), (other, o_other, wo_o, 0)):
+        rk, rv = oracle.align(f(seg.base_k), f(seg.base_v), [f(a) for a in seg.anchor_dk], [f(a) for a in seg.anchor_dv],
+                              wo, delta, w.rope_theta, gran=oracle.GRAN_SEGMENT)
+        check_close(f(out[0]), rk, w.dtype, "K^")
+        check_close(f(out[1]), rv, w.dtype, "V^")
