@@ -3,9 +3,10 @@
 
 A step is one pass of the whole hot path over the Llama-3-8B-shaped five-agent workload
 (workloads.LLAMA8B_5AGENTS): for each of the 5 agents, 4 peer segments of 512 tokens are
-matched against their 8-anchor pools (kvcomm_anchor_weights), re-positioned and offset-
-corrected into the agent's cache (kvcomm_align_kv), and the agent's 512 suffix queries then
-attend over the 3072-token cache (kvcomm_suffix_attn).  All inputs are synthetic, seeded and
+matched against their 8-anchor pools (kvcomm_anchor_weights_batch, one launch per stage for the
+four segments), re-positioned and offset-corrected into the agent's cache (kvcomm_align_kv_batch,
+one launch), and the agent's 512 suffix queries then attend over the 3072-token cache
+(kvcomm_suffix_attn).  All inputs are synthetic, seeded and
 resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = aligned KV tokens per second of the whole step (alignment
@@ -28,7 +29,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
 # HBM bytes per launch on this workload (read + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
 # (profiles/bench_llama8b_5agents_hbm_traffic.md).  Not measured live: counters need the profiler.
-HBM_TRAFFIC_BYTES = {"align_kv": 604122828 + 67108866, "anchor_weights": 302106675 + 2097294 + 2180060 + 20512,
+HBM_TRAFFIC_BYTES = {"align_kv": 4 * (604122828 + 67108866), "anchor_weights": 4 * (302106675 + 2097294 + 2180060 + 20512),
                      "suffix_attn": 537169465 + 134219516}
 
 
@@ -113,8 +114,20 @@ def main():
 
     agents = [workloads.make_agent(w, a, dev) for a in range(w.n_agents)]
     outs = [torch.empty_like(ag.q) for ag in agents]
-    scratches = [[hotpath.Scratch(model, w.seg_len, w.n_anchors, kv.W_TOKEN, dev) for _ in range(w.n_segments)]
+    scratches = [hotpath.AgentScratch(model, [w.seg_len] * w.n_segments, [w.n_anchors] * w.n_segments, kv.W_TOKEN, dev)
                  for _ in agents]
+    # job lists of the batched calls: built once, the timed loop only marshals and launches
+    wjobs, ajobs = [], []
+    for ag, sc in zip(agents, scratches):
+        wjobs.append([dict(seg_base_k=seg.base_k, anchor_base_k=seg.anchor_k, anchor_len=seg.anchor_len,
+                           weights_out=sc.weights[j], nearest_out=sc.nearest[j], selected_out=sc.selected[j])
+                      for j, seg in enumerate(ag.segments)])
+        ajobs.append([dict(base_k=seg.base_k, base_v=seg.base_v, anchor_dk=seg.anchor_dk, anchor_dv=seg.anchor_dv,
+                           anchor_len=seg.anchor_len, weights=sc.weights[j], delta_pos=seg.delta_pos,
+                           anchor_delta_pos=seg.anchor_delta_pos,
+                           out_k=ag.cache_k[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len],
+                           out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len])
+                      for j, seg in enumerate(ag.segments)])
     torch.cuda.synchronize()
 
     ev = {"weights": [], "align": [], "attn": []}
@@ -130,17 +143,11 @@ def main():
         ev[kind].append((e0, e1))
 
     def step(record):
+        # per agent: all four segments matched in one launch per stage, aligned in one launch, then attention
         for ai, ag in enumerate(agents):
-            for j, seg in enumerate(ag.segments):
-                p0 = w.seg_offset(j)
-                sc = scratches[ai][j]
-                ok, ov = ag.cache_k[:, :, p0:p0 + w.seg_len], ag.cache_v[:, :, p0:p0 + w.seg_len]
-                timed("weights", record, lambda: kv.kvcomm_anchor_weights(
-                    model, seg.base_k, seg.anchor_k, seg.anchor_len, w.temperature, kv.W_TOKEN, sc.weights,
-                    sc.nearest, sc.selected, sc.workspace))
-                timed("align", record, lambda: kv.kvcomm_align_kv(
-                    model, seg.base_k, seg.base_v, seg.anchor_dk, seg.anchor_dv, sc.weights, seg.delta_pos, ok, ov,
-                    seg.anchor_len, seg.anchor_delta_pos))
+            timed("weights", record, lambda: kv.kvcomm_anchor_weights_batch(
+                model, wjobs[ai], w.temperature, kv.W_TOKEN, workspace=scratches[ai].workspace))
+            timed("align", record, lambda: kv.kvcomm_align_kv_batch(model, ajobs[ai], kv.W_TOKEN))
             timed("attn", record, lambda: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
                                                                 out=outs[ai]))
 
@@ -157,7 +164,7 @@ def main():
     def avg_ms(kind):
         return sum(a.elapsed_time(b) for a, b in ev[kind]) / len(ev[kind]) if ev[kind] else None
 
-    seg_w = workloads.scaled(w, n_agents=1, n_segments=1)   # one launch = one segment
+    seg_w = workloads.scaled(w, n_agents=1)                 # one align / weights launch = the segments of one agent
     agent_w = workloads.scaled(w, n_agents=1)                # one attention launch = one agent
     kernels = {}
     t_align, t_weights, t_attn = avg_ms("align"), avg_ms("weights"), avg_ms("attn")
@@ -178,8 +185,8 @@ def main():
                                   "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn,
                                   "flops_per_launch": agent_w.attn_flops(), "traffic": HBM_TRAFFIC_BYTES["suffix_attn"]}
     # dominant kernel = the one with the largest share of a step
-    share = {"align_kv": (t_align or 0) * w.n_agents * w.n_segments,
-             "anchor_weights": (t_weights or 0) * w.n_agents * w.n_segments,
+    share = {"align_kv": (t_align or 0) * w.n_agents,
+             "anchor_weights": (t_weights or 0) * w.n_agents,
              "suffix_attn": (t_attn or 0) * w.n_agents}
     dominant = max(share, key=share.get) if kernels else None
     roofline = None
@@ -205,7 +212,7 @@ def main():
                    "seg_len": w.seg_len, "n_anchors": w.n_anchors, "n_ctx": w.n_ctx, "tq": w.tq,
                    "layers": w.n_layers, "kv_heads": w.n_kv_heads, "q_heads": w.n_q_heads, "head_dim": w.head_dim,
                    "aligned_tokens_per_step": w.aligned_tokens},
-        "align_tokens_per_s": (w.aligned_tokens / ((t_align + t_weights) * w.n_agents * w.n_segments * 1e-3)
+        "align_tokens_per_s": (w.aligned_tokens / ((t_align + t_weights) * w.n_agents * 1e-3)
                                if t_align and t_weights else None),
         "suffix_attn_tflops": kernels.get("suffix_attn", {}).get("achieved"),
         "roofline": roofline,

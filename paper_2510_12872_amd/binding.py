@@ -12,7 +12,8 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libkvcomm.so")
+# KVCOMM_LIBRARY selects another build of the same library (e.g. a tuning variant); default: the in-tree build
+_LIB_PATH = os.environ.get("KVCOMM_LIBRARY") or os.path.join(_HERE, "libkvcomm.so")
 
 W_TOKEN = 0
 W_LAYER_HEAD_TOKEN = 1
