@@ -29,8 +29,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
 # HBM bytes per launch on this workload (read + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
 # (profiles/bench_llama8b_5agents_hbm_traffic.md).  Not measured live: counters need the profiler.
-HBM_TRAFFIC_BYTES = {"align_kv": 4 * (604122828 + 67108866), "anchor_weights": 4 * (302106675 + 2097294 + 2180060 + 20512),
-                     "suffix_attn": 537169465 + 134219516}
+HBM_TRAFFIC_BYTES = {"align_kv": 2416138240 + 268435456, "anchor_weights": 1208109056 + 8389632 + 8493056 + 81920,
+                     "suffix_attn": 537579520 + 134217728}
 
 
 def cpu_baseline(w):
