@@ -30,7 +30,10 @@ using namespace kvc;
 #endif
 
 #ifndef KVC_ALIGN_INFLIGHT
-#define KVC_ALIGN_INFLIGHT 4
+#define KVC_ALIGN_INFLIGHT 2
+#endif
+#ifndef KVC_ALIGN_WPE
+#define KVC_ALIGN_WPE 4   // wavefronts per SIMD the register budget is sized for (measured best: 4 with 2 anchors in flight)
 #endif
 
 constexpr int kBlock = 256;
@@ -70,7 +73,7 @@ struct AlignParams {
 static_assert(sizeof(AlignParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 template <typename T, int LPR>
-__global__ __launch_bounds__(kBlock) void align_kernel(const AlignParams p)
+__global__ __launch_bounds__(kBlock, KVC_ALIGN_WPE) void align_kernel(const AlignParams p)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int HALF = LPR * EPV;  // D / 2
