@@ -68,6 +68,15 @@ def _load():
         lib.kvo_weights_from_sim.restype = None
         lib.kvo_weights_nearest.argtypes = [dp, ip, ctypes.c_int, ctypes.c_size_t, dp, ip]
         lib.kvo_weights_nearest.restype = None
+        ub = ctypes.POINTER(ctypes.c_ubyte)
+        lib.kvo_e4m3_decode.argtypes = [ctypes.c_ubyte]
+        lib.kvo_e4m3_decode.restype = ctypes.c_double
+        lib.kvo_e4m3_encode.argtypes = [ctypes.c_double]
+        lib.kvo_e4m3_encode.restype = ctypes.c_ubyte
+        lib.kvo_quantize.argtypes = [dp, ctypes.c_size_t, ctypes.c_double, ub]
+        lib.kvo_quantize.restype = None
+        lib.kvo_dequantize.argtypes = [ub, ctypes.c_size_t, ctypes.c_double, dp]
+        lib.kvo_dequantize.restype = None
         lib.kvo_num_threads.argtypes = []
         lib.kvo_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -249,3 +258,29 @@ def weights_nearest(dist, selected):
     nearest = np.zeros(n, dtype=np.intc)
     _load().kvo_weights_nearest(_dptr(dist), _iptr(selected), A, n, _dptr(w), _iptr(nearest))
     return w, nearest
+
+
+def e4m3_decode(byte):
+    """One OCP E4M3 byte -> float (NaN for S.1111.111)."""
+    return float(_load().kvo_e4m3_decode(int(byte) & 0xff))
+
+
+def e4m3_encode(x):
+    """Nearest E4M3 byte (ties to even, saturating at +-448)."""
+    return int(_load().kvo_e4m3_encode(float(x)))
+
+
+def quantize(x, scale):
+    """Array -> uint8 array of E4M3 codes of x / scale."""
+    x = _f64(x)
+    out = np.empty(x.shape, dtype=np.uint8)
+    _load().kvo_quantize(_dptr(x), x.size, float(scale), out.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)))
+    return out
+
+
+def dequantize(b, scale):
+    """uint8 array of E4M3 codes -> float64 array scale * value."""
+    b = np.ascontiguousarray(np.asarray(b, dtype=np.uint8))
+    out = np.empty(b.shape, dtype=np.float64)
+    _load().kvo_dequantize(b.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)), b.size, float(scale), _dptr(out))
+    return out

@@ -403,3 +403,56 @@ void kvo_weights_nearest(const double *dist, const int *selected, int A, size_t 
         for (int a = 0; a < A; ++a) w[(size_t)a * n + j] = (a == best) ? 1.0 : 0.0;
     }
 }
+
+/* ------------------------------------------------------------------------- */
+/* O9.  Compressed anchor deviations (the appendix on memory cost notes that the deviation
+ * tensors are small in magnitude, about half of the elements below 0.1, and names their
+ * compression as future work).  Storage format used here: one byte per element in the OCP
+ * 8-bit floating-point format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+ * infinities; S.1111.111 is NaN; largest finite value 448; subnormals m/8 * 2^-6), times a
+ * power-of-two scale per tensor:  value = scale * e4m3(byte).
+ * Encoding rounds x / scale to the nearest representable value, ties to the even mantissa,
+ * and saturates at +-448.  This is lossy: relative error at most 2^-4 for |x| >= scale * 2^-6,
+ * absolute error at most scale * 2^-10 below that.                                          */
+double kvo_e4m3_decode(unsigned char b)
+{
+    int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+unsigned char kvo_e4m3_encode(double x)
+{
+    if (isnan(x)) return 0x7f;
+    unsigned char sign = (unsigned char)(signbit(x) ? 0x80 : 0x00);
+    double a = fabs(x);
+    if (a >= 448.0) return (unsigned char)(sign | 0x7e);
+    /* spacing of the grid around a: 2^-9 in the subnormal range and the first binade, else 2^(floor(log2 a) - 3) */
+    int ex;
+    (void)frexp(a, &ex);          /* a = f * 2^ex, f in [0.5, 1)  ->  floor(log2 a) = ex - 1 */
+    int e_unb = ex - 1;
+    if (a == 0.0 || e_unb < -6) e_unb = -6;
+    double step = ldexp(1.0, e_unb - 3);
+    double q = a / step;          /* exact: division by a power of two */
+    double r = floor(q);
+    double frac = q - r;
+    if (frac > 0.5 || (frac == 0.5 && fmod(r, 2.0) == 1.0)) r += 1.0;
+    double v = r * step;          /* a grid point, possibly the first of the next binade */
+    /* turn the value back into bits by searching the (monotone) code table: plain and obviously right */
+    for (int code = 0; code < 0x7f; ++code)
+        if (kvo_e4m3_decode((unsigned char)code) == v) return (unsigned char)(sign | code);
+    return (unsigned char)(sign | 0x7e);
+}
+
+void kvo_quantize(const double *x, size_t n, double scale, unsigned char *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = kvo_e4m3_encode(x[i] / scale);
+}
+
+void kvo_dequantize(const unsigned char *b, size_t n, double scale, double *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = scale * kvo_e4m3_decode(b[i]);
+}

@@ -142,3 +142,52 @@ def test_nearest_is_argmin_one_hot_and_limit_of_softmax():
     dm = np.where(sel[:, None] == 1, d2, np.inf)
     assert np.array_equal(near2, np.argmin(dm, axis=0))
     assert np.all(oracle.weights_nearest(d2, [0] * 5)[1] == -1)
+
+
+# ----------------------------------------------------------------------------- O9
+def test_e4m3_codec_against_library_and_closed_forms():
+    """The 8-bit storage format of compressed deviations: every code against torch's float8_e4m3fn (an
+    independent implementation of the OCP format), hand-computed codes, ties to even, saturation."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    mine = np.array([oracle.e4m3_decode(c) for c in codes])
+    assert np.isnan(mine[0x7f]) and np.isnan(mine[0xff]) and np.isnan(lib[0x7f])
+    ok = ~np.isnan(lib)
+    assert np.array_equal(mine[ok], lib[ok])
+    # closed forms: 0 0111 000 = 1; largest finite 0 1111 110 = 448; smallest subnormal 2^-9; smallest normal 2^-6
+    assert oracle.e4m3_decode(0x38) == 1.0 and oracle.e4m3_decode(0x7e) == 448.0
+    assert oracle.e4m3_decode(0x01) == 2.0 ** -9 and oracle.e4m3_decode(0x08) == 2.0 ** -6
+    assert oracle.e4m3_decode(0xb8) == -1.0
+    # encoding: exact values round-trip; random values agree with the library inside the range
+    for c in codes[ok]:
+        v = oracle.e4m3_decode(c)
+        if v == 0.0:
+            continue
+        assert oracle.e4m3_encode(v) == c
+    x = np.concatenate([rng.standard_normal(4000) * 0.05 * 1024, rng.uniform(-448, 448, 2000),
+                        rng.uniform(-2 ** -6, 2 ** -6, 2000)])
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.e4m3_encode(v) for v in x], dtype=np.uint8)
+    same_value = np.array([oracle.e4m3_decode(a) == oracle.e4m3_decode(b) for a, b in zip(got, want)])
+    assert same_value.all()                                  # (+0 / -0 codes may differ, values may not)
+    # ties go to the even mantissa: halfway 1.0|1.125 -> 1.0 ; halfway 1.125|1.25 -> 1.25 ; subnormal half steps
+    assert oracle.e4m3_encode(1.0625) == 0x38 and oracle.e4m3_encode(1.1875) == 0x3a
+    assert oracle.e4m3_encode(2.0 ** -10) == 0x00 and oracle.e4m3_encode(3 * 2.0 ** -10) == 0x02
+    # just above a tie rounds up, saturation, sign
+    assert oracle.e4m3_encode(1.0626) == 0x39
+    assert oracle.e4m3_encode(1e6) == 0x7e and oracle.e4m3_encode(-1e6) == 0xfe and oracle.e4m3_encode(449.0) == 0x7e
+    assert oracle.e4m3_encode(-0.3) == (0x80 | oracle.e4m3_encode(0.3))
+
+
+def test_quantize_error_bound_and_scale():
+    x = rng.standard_normal(5000) * 0.05
+    scale = 2.0 ** -10
+    q = oracle.quantize(x, scale)
+    y = oracle.dequantize(q, scale)
+    big = np.abs(x) >= scale * 2.0 ** -6
+    assert np.all(np.abs(y[big] - x[big]) <= np.abs(x[big]) * 2.0 ** -4)
+    assert np.all(np.abs(y[~big] - x[~big]) <= scale * 2.0 ** -10)
+    # scaling input and scale together leaves the codes unchanged (the scale is a power of two)
+    assert np.array_equal(oracle.quantize(x * 4, scale * 4), q)
+    assert np.array_equal(oracle.dequantize(q, 2 * scale), 2 * y)
