@@ -287,6 +287,35 @@ int kvcomm_capture_offsets(const kvcomm_model *model, kvcomm_tensor base_k, kvco
                            kvcomm_tensor real_k, kvcomm_tensor real_v, int32_t seg_len, int32_t delta_pos,
                            kvcomm_tensor out_dk, kvcomm_tensor out_dv, void *stream);
 
+/* --------------------------------------------------------------------------------------
+ * Compressed anchor deviations (the appendix on memory cost observes that the deviation
+ * tensors are small in magnitude and names their compression as future work).  Storage:
+ * one byte per element in the OCP 8-bit floating-point format E4M3 (1 sign, 4 exponent bits
+ * with bias 7, 3 mantissa bits, no infinities, largest finite value 448) times a power-of-two
+ * scale per tensor:  value = scale * e4m3(byte).  LOSSY: relative error at most 2^-4 for
+ * |x| >= scale * 2^-6, absolute error at most scale * 2^-10 below; |x| > 448 * scale saturates.
+ * Byte tensors are described by kvcomm_tensor with strides in bytes; pointers 16-byte aligned,
+ * strides multiples of 16.
+ *
+ * kvcomm_quantize_deltas: in [L, Hkv, n_tokens, D] of the model dtype -> out, same shape, E4M3
+ * bytes of in / scale rounded to nearest (ties to even).  scale must be a power of two
+ * (else KVCOMM_EINVAL): the division is then exact and the codes are reproducible bit for bit.
+ *
+ * kvcomm_align_kv_q8: kvcomm_align_kv with anchor_dk / anchor_dv pointing at E4M3 tensors laid
+ * out by `anchor_layout` (bytes) and HOST arrays anchor_scale_k / anchor_scale_v [n_anchors] of
+ * their scales.  Everything else (selection, rotation of deviations recorded elsewhere, fp32
+ * accumulation in anchor order, one rounding at the store) is as in kvcomm_align_kv.          */
+int kvcomm_quantize_deltas(const kvcomm_model *model, kvcomm_tensor in, int32_t n_tokens, float scale,
+                           kvcomm_tensor out, void *stream);
+
+int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran,
+                       kvcomm_tensor base_k, kvcomm_tensor base_v, int32_t seg_len,
+                       const void *const *anchor_dk, const void *const *anchor_dv,
+                       kvcomm_tensor anchor_layout, const int32_t *anchor_len,
+                       const float *anchor_scale_k, const float *anchor_scale_v, int32_t n_anchors,
+                       const float *weights, int32_t delta_pos, const int32_t *anchor_delta_pos,
+                       kvcomm_tensor out_k, kvcomm_tensor out_v, void *stream);
+
 /* Human-readable name of a kvcomm_status; never NULL. */
 const char *kvcomm_status_string(int status);
 

@@ -127,6 +127,12 @@ def load_library():
     lib.kvcomm_anchor_weights_batch.argtypes = [mp, i32, i32, f32, _CTensor, ctypes.POINTER(_CWeightsJob), i32, vp,
                                                 sz, vp]
     lib.kvcomm_anchor_weights_batch.restype = ctypes.c_int
+    lib.kvcomm_quantize_deltas.argtypes = [mp, _CTensor, i32, f32, _CTensor, vp]
+    lib.kvcomm_quantize_deltas.restype = ctypes.c_int
+    lib.kvcomm_align_kv_q8.argtypes = [mp, i32, _CTensor, _CTensor, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       _CTensor, ctypes.POINTER(i32), ctypes.POINTER(f32), ctypes.POINTER(f32), i32,
+                                       vp, i32, ctypes.POINTER(i32), _CTensor, _CTensor, vp]
+    lib.kvcomm_align_kv_q8.restype = ctypes.c_int
     lib.kvcomm_status_string.argtypes = [ctypes.c_int]
     lib.kvcomm_status_string.restype = ctypes.c_char_p
     lib.kvcomm_version.argtypes = []
@@ -425,3 +431,56 @@ def kvcomm_align_kv_batch(model, jobs, gran=W_TOKEN, stream=None):
     _check(lib.kvcomm_align_kv_batch(ctypes.byref(model.c()), gran,
                                      layout if layout is not None else _CTensor(None, 0, 0, 0), cjobs, n,
                                      _stream_ptr(stream)))
+
+
+def _desc_q8(t, what):
+    """[layer, head, token, channel] uint8 tensor of E4M3 codes -> kvcomm_tensor (strides in bytes)."""
+    if t.dim() != 4 or t.dtype != torch.uint8 or not t.is_cuda or t.stride(3) != 1:
+        raise KVCommError(-1, f"{what}: expected a 4-d uint8 device tensor with contiguous channels")
+    return _CTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def kvcomm_quantize_deltas(model, x, scale, out=None, stream=None):
+    """Stored deviation x [L,Hkv,n,D] (model dtype) -> E4M3 codes (uint8) of x / scale; scale a power of two."""
+    lib = load_library()
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(lib.kvcomm_quantize_deltas(ctypes.byref(model.c()), _desc(x, model.dtype, "x"), x.shape[2], float(scale),
+                                      _desc_q8(out, "out"), _stream_ptr(stream)))
+    return out
+
+
+def kvcomm_align_kv_q8(model, base_k, base_v, anchor_dk8, anchor_dv8, scale_k, scale_v, weights, delta_pos, out_k,
+                       out_v, anchor_len=None, anchor_delta_pos=None, gran=W_TOKEN, stream=None):
+    """kvcomm_align_kv with E4M3-compressed deviations (uint8 tensors) and their per-anchor scales."""
+    lib = load_library()
+    seg_len = base_k.shape[2]
+    A = len(anchor_dk8)
+    if len(anchor_dv8) != A or len(scale_k) != A or len(scale_v) != A:
+        raise KVCommError(-1, "anchor lists and scales differ in length")
+    if A:
+        layout = _desc_q8(anchor_dk8[0], "anchor_dk8")
+        for a in list(anchor_dk8) + list(anchor_dv8):
+            if not _same_layout(layout, _desc_q8(a, "anchor deviations")):
+                raise KVCommError(-1, "all compressed anchors must share one layout")
+        pk = (ctypes.c_void_p * A)(*[a.data_ptr() for a in anchor_dk8])
+        pv = (ctypes.c_void_p * A)(*[a.data_ptr() for a in anchor_dv8])
+        lens = (ctypes.c_int32 * A)(*[int(x) for x in (anchor_len if anchor_len is not None
+                                                        else [a.shape[2] for a in anchor_dk8])])
+        sk = (ctypes.c_float * A)(*[float(x) for x in scale_k])
+        sv = (ctypes.c_float * A)(*[float(x) for x in scale_v])
+        if weights is None or weights.dtype != torch.float32 or not weights.is_contiguous():
+            raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
+        if weights.numel() != kvcomm_weight_slots(model, seg_len, gran) * A:
+            raise KVCommError(-1, "weights: wrong number of elements for this granularity")
+    else:
+        layout, pk, pv, lens, sk, sv = _CTensor(None, 0, 0, 0), None, None, None, None, None
+    adp = None
+    if anchor_delta_pos is not None:
+        adp = (ctypes.c_int32 * max(A, 1))(*[int(x) for x in anchor_delta_pos])
+    _check(lib.kvcomm_align_kv_q8(ctypes.byref(model.c()), gran, _desc(base_k, model.dtype, "base_k"),
+                                  _desc(base_v, model.dtype, "base_v"), seg_len, pk, pv, layout, lens, sk, sv, A,
+                                  None if weights is None else weights.data_ptr(), int(delta_pos), adp,
+                                  _desc(out_k, model.dtype, "out_k"), _desc(out_v, model.dtype, "out_v"),
+                                  _stream_ptr(stream)))
+    return out_k, out_v

@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libkvcomm.so")
-SOURCES = ["align_kv.hip", "anchor_weights.hip", "anchor_update.hip", "suffix_attn.hip", "status.hip"]
+SOURCES = ["align_kv.hip", "anchor_weights.hip", "anchor_update.hip", "delta_q8.hip", "suffix_attn.hip", "status.hip"]
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 instructions.
 HIPCC_FLAGS = [

@@ -1,0 +1,384 @@
+// Compressed anchor deviations: one byte per element in the OCP 8-bit floating-point format E4M3 times a
+// power-of-two scale per tensor (the appendix on memory cost notes that the deviation tensors are small
+// in magnitude and names their compression as future work).  The stored deviations are 2 * A of the
+// 2 * (A + 2) rows the offset approximation moves per (layer, head, token), so halving them cuts the
+// HBM traffic of that step from 2*D*es*(A+2) to D*(4*es + 2*A) bytes per row (40 % less for bf16, A = 8).
+//   kvcomm_quantize_deltas   stored deviation (model dtype) -> E4M3 bytes: x / scale rounded to nearest even,
+//                            saturating at +-448 (lossy: relative error <= 2^-4 above scale * 2^-6);
+//   kvcomm_align_kv_q8       kvcomm_align_kv reading E4M3 deviations; the scale is folded into the anchor
+//                            weight, so the inner loop is that of the uncompressed kernel plus the unpacking.
+// gfx950's v_cvt_pk_f32_fp8 / v_cvt_pk_fp8_f32 implement exactly this format; the encoder clamps first, so
+// the hardware's own overflow behaviour never matters.
+#include <math.h>
+
+#include "kvcomm_device.h"
+
+namespace {
+
+using namespace kvc;
+
+constexpr int kBlock = 256;
+constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
+constexpr int kMaxHalf = 128;
+
+// EPV consecutive E4M3 bytes -> floats.
+template <int EPV>
+__device__ __forceinline__ void unpack_q8(const uint32_t (&raw)[EPV / 4], float (&out)[EPV])
+{
+#pragma unroll
+    for (int w = 0; w < EPV / 4; ++w) {
+        const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(raw[w], false);
+        const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(raw[w], true);
+        out[4 * w] = a[0];
+        out[4 * w + 1] = a[1];
+        out[4 * w + 2] = b[0];
+        out[4 * w + 3] = b[1];
+    }
+}
+
+template <int EPV>
+__device__ __forceinline__ void load_q8(const uint8_t *p, uint32_t (&raw)[EPV / 4])
+{
+    if constexpr (EPV == 8) {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+        raw[0] = v[0];
+        raw[1] = v[1];
+    } else {
+        raw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+    }
+}
+
+// ------------------------------------------------------------------------------ quantise
+struct QuantParams {
+    const void *in;
+    uint8_t *out;
+    Strides s_in, s_out;
+    int32_t H, S, LH, n_token_tiles;
+    float inv_scale;
+};
+
+template <typename T, int LPR>  // LPR lanes per row, each EPV elements
+__global__ __launch_bounds__(kBlock) void quantize_kernel(const QuantParams p)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr int RPB = kBlock / LPR;
+    const int row = threadIdx.x / LPR, lir = threadIdx.x % LPR;
+    const int tile = blockIdx.x % p.n_token_tiles;
+    const int lh = blockIdx.x / p.n_token_tiles;
+    const int t = tile * RPB + row;
+    if (t >= p.S) return;
+    const int l = lh / p.H, h = lh % p.H;
+    const T *xp = static_cast<const T *>(p.in) + l * p.s_in.layer + h * p.s_in.head + t * p.s_in.token + lir * EPV;
+    float x[EPV];
+    unpack<T>(load16_stream(xp), x);
+    uint32_t w[EPV / 4];
+#pragma unroll
+    for (int i = 0; i < EPV / 4; ++i) {
+        float c[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = fminf(fmaxf(x[4 * i + e] * p.inv_scale, -448.f), 448.f);  // NaN stays NaN
+        int packed = 0;
+        packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], packed, false);
+        packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], packed, true);
+        w[i] = (uint32_t)packed;
+    }
+    uint8_t *yp = p.out + l * p.s_out.layer + h * p.s_out.head + t * p.s_out.token + lir * EPV;
+    if constexpr (EPV == 8) {
+        const u32x2 v = {w[0], w[1]};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(yp));
+    } else {
+        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(yp));
+    }
+}
+
+// --------------------------------------------------------------------------------- align
+struct AlignQ8Params {
+    const void *base[2];   // [0] keys, [1] values
+    void *out[2];
+    Strides s_base[2], s_out[2], s_anc;   // s_anc in bytes (= elements of the E4M3 tensors)
+    const float *weights;
+    int32_t H, S, LH;
+    int32_t w_pitch, n_sel, gran;
+    int32_t lh_per_block, n_token_tiles;
+    int32_t n_tab, base_tab;
+    int32_t tab_delta[kMaxTab];
+    const uint8_t *anc[2][KVCOMM_MAX_ANCHORS];
+    float scale[2][KVCOMM_MAX_ANCHORS];   // [0] key, [1] value deviation scale of a selected anchor
+    uint8_t col[KVCOMM_MAX_ANCHORS];
+    uint8_t tab[KVCOMM_MAX_ANCHORS];
+    double inv_freq[kMaxHalf];
+};
+static_assert(sizeof(AlignQ8Params) <= 4096, "kernel arguments are limited to 4 KB");
+
+// Work split as in align_kernel: LPR = D / (2 * EPV) lanes per row, lane r owns channels [r*EPV, r*EPV+EPV)
+// of both halves; a block is 256 / LPR tokens of a run of (layer, head) pairs of ONE tensor.
+template <typename T, int LPR>
+__global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params p)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr int HALF = LPR * EPV;
+    constexpr int RPB = kBlock / LPR;
+
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float2 *cs = reinterpret_cast<float2 *>(smem_raw);                        // [n_tab][HALF]
+    float *w_lds = reinterpret_cast<float *>(smem_raw) + 2 * p.n_tab * HALF;  // [RPB][n_sel], scale folded in
+
+    const int tid = threadIdx.x;
+    const int row = tid / LPR, lir = tid % LPR;
+    const int tile = blockIdx.x % p.n_token_tiles;
+    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int which = blockIdx.y;
+    const bool is_k = which == 0;
+    const int t = tile * RPB + row;
+    const bool valid = t < p.S;
+    const int lh0 = chunk * p.lh_per_block;
+    const int lh1 = min(lh0 + p.lh_per_block, p.LH);
+
+    if (is_k)
+        for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock)
+            cs[idx] = rope_cos_sin(p.tab_delta[idx / HALF], p.inv_freq[idx % HALF]);
+    if (p.gran != KVCOMM_W_LAYER_HEAD_TOKEN) {
+        for (int idx = tid; idx < RPB * p.n_sel; idx += kBlock) {
+            const int r = idx / p.n_sel, a = idx % p.n_sel;
+            const int tt = tile * RPB + r;
+            const int64_t slot = p.gran == KVCOMM_W_TOKEN ? tt : 0;
+            w_lds[idx] = tt < p.S ? p.weights[slot * p.w_pitch + p.col[a]] * p.scale[which][a] : 0.f;
+        }
+    }
+    __syncthreads();
+    if (!valid) return;
+
+    const bool rot_base = is_k && p.base_tab != 0;
+    float bc[EPV], bs[EPV];
+    if (rot_base) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            const float2 v = cs[(p.base_tab - 1) * HALF + lir * EPV + e];
+            bc[e] = v.x;
+            bs[e] = v.y;
+        }
+    }
+    const T *bp = static_cast<const T *>(p.base[which]);
+    T *op = static_cast<T *>(p.out[which]);
+    const Strides sb = p.s_base[which], so = p.s_out[which];
+    const int64_t col0 = (int64_t)lir * EPV;
+
+    for (int lh = lh0; lh < lh1; ++lh) {
+        const int l = lh / p.H, h = lh % p.H;
+        const T *xp = bp + l * sb.layer + h * sb.head + t * sb.token + col0;
+        const u32x4 rlo = load16_stream(xp), rhi = load16_stream(xp + HALF);
+        const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + col0;
+        const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN ? p.weights + ((int64_t)lh * p.S + t) * p.w_pitch : nullptr;
+
+        float lo[EPV], hi[EPV];
+        unpack<T>(rlo, lo);
+        unpack<T>(rhi, hi);
+        if (rot_base) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                const float a = lo[e], b = hi[e];
+                lo[e] = a * bc[e] - b * bs[e];
+                hi[e] = b * bc[e] + a * bs[e];
+            }
+        }
+        auto accumulate = [&](int a, const uint32_t (&rdlo)[EPV / 4], const uint32_t (&rdhi)[EPV / 4]) {
+            const float w = wrow ? wrow[p.col[a]] * p.scale[which][a] : w_lds[row * p.n_sel + a];
+            float dlo[EPV], dhi[EPV];
+            unpack_q8<EPV>(rdlo, dlo);
+            unpack_q8<EPV>(rdhi, dhi);
+            const int tb = is_k ? p.tab[a] : 0;
+            if (tb) {
+                const float2 *tcs = cs + (tb - 1) * HALF + lir * EPV;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const float2 v = tcs[e];
+                    const float x = dlo[e], y = dhi[e];
+                    dlo[e] = x * v.x - y * v.y;
+                    dhi[e] = y * v.x + x * v.y;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                lo[e] += w * dlo[e];
+                hi[e] += w * dhi[e];
+            }
+        };
+        // four anchors (eight independent loads) in flight
+        int a = 0;
+        for (; a + 4 <= p.n_sel; a += 4) {
+            uint32_t x[4][2][EPV / 4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint8_t *d = p.anc[which][a + u] + aoff;
+                load_q8<EPV>(d, x[u][0]);
+                load_q8<EPV>(d + HALF, x[u][1]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
+        }
+        for (; a < p.n_sel; ++a) {
+            uint32_t x0[EPV / 4], x1[EPV / 4];
+            const uint8_t *d = p.anc[which][a] + aoff;
+            load_q8<EPV>(d, x0);
+            load_q8<EPV>(d + HALF, x1);
+            accumulate(a, x0, x1);
+        }
+        T *yp = op + l * so.layer + h * so.head + t * so.token + col0;
+        store16_stream(yp, pack<T>(lo));
+        store16_stream(yp + HALF, pack<T>(hi));
+    }
+}
+
+template <typename T, int LPR>
+int launch_align_q8(const AlignQ8Params &p, int n_blocks, hipStream_t stream)
+{
+    constexpr int HALF = LPR * Elem<T>::EPV;
+    constexpr int RPB = kBlock / LPR;
+    const size_t lds = sizeof(float2) * (size_t)p.n_tab * HALF + sizeof(float) * (size_t)RPB * p.n_sel;
+    hipLaunchKernelGGL((align_q8_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
+    return launch_status();
+}
+
+// Byte tensors: pointer 16-byte aligned, strides multiples of 16 bytes.
+int check_tensor_q8(const kvcomm_tensor &t, bool need_ptr)
+{
+    if (need_ptr && (!t.ptr || !aligned16(t.ptr))) return KVCOMM_EINVAL;
+    if (t.stride_layer < 0 || t.stride_head < 0 || t.stride_token < 0) return KVCOMM_EINVAL;
+    if (t.stride_layer % 16 || t.stride_head % 16 || t.stride_token % 16) return KVCOMM_EINVAL;
+    return KVCOMM_OK;
+}
+
+bool power_of_two(float s)
+{
+    if (!(s > 0.f) || !isfinite(s)) return false;
+    int e;
+    return frexpf(s, &e) == 0.5f;
+}
+
+}  // namespace
+
+extern "C" int kvcomm_quantize_deltas(const kvcomm_model *model, kvcomm_tensor in, int32_t n_tokens, float scale,
+                                      kvcomm_tensor out, void *stream)
+{
+    int st = check_model(model);
+    if (st) return st;
+    if (n_tokens <= 0 || !power_of_two(scale)) return KVCOMM_EINVAL;
+    const int dt = model->dtype;
+    if ((st = check_tensor(in, dt, true)) || (st = check_tensor_q8(out, true))) return st;
+    QuantParams p{};
+    p.in = in.ptr;
+    p.out = static_cast<uint8_t *>(out.ptr);
+    p.s_in = strides_of(in);
+    p.s_out = strides_of(out);
+    p.H = model->n_kv_heads;
+    p.S = n_tokens;
+    p.LH = model->n_layers * model->n_kv_heads;
+    p.inv_scale = 1.f / scale;
+    const int lpr = model->head_dim / (16 / elem_size(dt));
+    const int rpb = kBlock / lpr;
+    p.n_token_tiles = (n_tokens + rpb - 1) / rpb;
+    const int64_t n_blocks = (int64_t)p.n_token_tiles * p.LH;
+    if (n_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = KVCOMM_EUNSUPPORTED;
+    if (dt == KVCOMM_BF16) {
+        switch (lpr) {
+            case 8: hipLaunchKernelGGL((quantize_kernel<bf16_t, 8>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 16: hipLaunchKernelGGL((quantize_kernel<bf16_t, 16>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 32: hipLaunchKernelGGL((quantize_kernel<bf16_t, 32>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+        }
+    } else {
+        switch (lpr) {
+            case 16: hipLaunchKernelGGL((quantize_kernel<float, 16>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 32: hipLaunchKernelGGL((quantize_kernel<float, 32>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 64: hipLaunchKernelGGL((quantize_kernel<float, 64>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+        }
+    }
+    return st ? st : launch_status();
+}
+
+extern "C" int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran, kvcomm_tensor base_k, kvcomm_tensor base_v,
+                                  int32_t seg_len, const void *const *anchor_dk, const void *const *anchor_dv,
+                                  kvcomm_tensor anchor_layout, const int32_t *anchor_len, const float *anchor_scale_k,
+                                  const float *anchor_scale_v, int32_t n_anchors, const float *weights,
+                                  int32_t delta_pos, const int32_t *anchor_delta_pos, kvcomm_tensor out_k,
+                                  kvcomm_tensor out_v, void *stream)
+{
+    int st = check_model(model);
+    if (st) return st;
+    if ((st = check_gran(gran))) return st;
+    if (seg_len <= 0 || n_anchors < 0) return KVCOMM_EINVAL;
+    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
+    const int dt = model->dtype;
+    if ((st = check_tensor(base_k, dt, true)) || (st = check_tensor(base_v, dt, true)) ||
+        (st = check_tensor(out_k, dt, true)) || (st = check_tensor(out_v, dt, true)))
+        return st;
+    if (n_anchors > 0) {
+        if (!anchor_dk || !anchor_dv || !anchor_len || !anchor_scale_k || !anchor_scale_v || !weights) return KVCOMM_EINVAL;
+        if ((st = check_tensor_q8(anchor_layout, false))) return st;
+    }
+    AlignQ8Params p{};
+    p.base[0] = base_k.ptr;
+    p.base[1] = base_v.ptr;
+    p.out[0] = out_k.ptr;
+    p.out[1] = out_v.ptr;
+    p.s_base[0] = strides_of(base_k);
+    p.s_base[1] = strides_of(base_v);
+    p.s_out[0] = strides_of(out_k);
+    p.s_out[1] = strides_of(out_v);
+    p.s_anc = strides_of(anchor_layout);
+    p.weights = weights;
+    p.H = model->n_kv_heads;
+    p.S = seg_len;
+    p.LH = model->n_layers * model->n_kv_heads;
+    p.w_pitch = n_anchors;
+    p.gran = gran;
+    for (int i = 0; i < model->head_dim / 2; ++i)
+        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
+    auto table_of = [&](int32_t d) -> int {
+        if (d == 0) return 0;
+        for (int r = 0; r < p.n_tab; ++r)
+            if (p.tab_delta[r] == d) return r + 1;
+        p.tab_delta[p.n_tab] = d;
+        return ++p.n_tab;
+    };
+    p.base_tab = table_of(delta_pos);
+    for (int a = 0; a < n_anchors; ++a) {
+        if (anchor_len[a] < 0) return KVCOMM_EINVAL;
+        if (anchor_len[a] < seg_len) continue;
+        if (!anchor_dk[a] || !anchor_dv[a] || !aligned16(anchor_dk[a]) || !aligned16(anchor_dv[a])) return KVCOMM_EINVAL;
+        if (!power_of_two(anchor_scale_k[a]) || !power_of_two(anchor_scale_v[a])) return KVCOMM_EINVAL;
+        const int s = p.n_sel++;
+        p.anc[0][s] = static_cast<const uint8_t *>(anchor_dk[a]);
+        p.anc[1][s] = static_cast<const uint8_t *>(anchor_dv[a]);
+        p.scale[0][s] = anchor_scale_k[a];
+        p.scale[1][s] = anchor_scale_v[a];
+        p.col[s] = (uint8_t)a;
+        p.tab[s] = (uint8_t)(anchor_delta_pos ? table_of(delta_pos - anchor_delta_pos[a]) : 0);
+    }
+    const int es = elem_size(dt);
+    const int lpr = model->head_dim / (2 * (16 / es));
+    const int rpb = kBlock / lpr;
+    p.n_token_tiles = (seg_len + rpb - 1) / rpb;
+    int n_chunks = (32768 + p.n_token_tiles - 1) / p.n_token_tiles;
+    if (n_chunks > p.LH) n_chunks = p.LH;
+    if (n_chunks < 1) n_chunks = 1;
+    p.lh_per_block = (p.LH + n_chunks - 1) / n_chunks;
+    n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
+    const int n_blocks = n_chunks * p.n_token_tiles;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == KVCOMM_BF16) {
+        switch (lpr) {
+            case 4: return launch_align_q8<bf16_t, 4>(p, n_blocks, s);
+            case 8: return launch_align_q8<bf16_t, 8>(p, n_blocks, s);
+            case 16: return launch_align_q8<bf16_t, 16>(p, n_blocks, s);
+        }
+    } else {
+        switch (lpr) {
+            case 8: return launch_align_q8<float, 8>(p, n_blocks, s);
+            case 16: return launch_align_q8<float, 16>(p, n_blocks, s);
+            case 32: return launch_align_q8<float, 32>(p, n_blocks, s);
+        }
+    }
+    return KVCOMM_EUNSUPPORTED;
+}

@@ -13,4 +13,4 @@ extern "C" const char *kvcomm_status_string(int status)
     }
 }
 
-extern "C" int kvcomm_version(void) { return 110; }
+extern "C" int kvcomm_version(void) { return 120; }

@@ -38,7 +38,7 @@ def test_header_symbols_are_exported(lib):
             "kvcomm_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in kvcomm.h but not exported"
-    assert lib.kvcomm_version() >= 110
+    assert lib.kvcomm_version() >= 120
     for st in (0, -1, -2, -3, -4, 17):
         assert lib.kvcomm_status_string(st)
 
@@ -158,6 +158,28 @@ def test_rule_predict_capture_argument_errors(lib):
     assert cap(mm=_model(head_dim=72)) == EUNSUPPORTED
     assert lib.kvcomm_capture_offsets(None, _tensor(), _tensor(), _tensor(), _tensor(), 16, 0, _tensor(), _tensor(),
                                       None) == EINVAL
+
+
+def test_compressed_deviation_argument_errors(lib):
+    m = _model()
+    q = lambda scale=2.0 ** -10, n=16, inp=None, out=None: lib.kvcomm_quantize_deltas(
+        ctypes.byref(m), inp or _tensor(), n, scale, out or _tensor(0x2000, st=128), None)
+    assert q(scale=0.003) == EINVAL and q(scale=0.0) == EINVAL and q(scale=-0.5) == EINVAL
+    assert q(scale=float("inf")) == EINVAL and q(scale=float("nan")) == EINVAL
+    assert q(n=0) == EINVAL
+    assert q(out=_tensor(0x2008, st=128)) == EINVAL           # byte tensors need 16-byte alignment too
+    assert q(out=_tensor(0x2000, st=72)) == EINVAL
+    assert q(inp=_tensor(ptr=None)) == EINVAL
+    parr = (ctypes.c_void_p * 2)(0x2000, 0x3000)
+    larr = (ctypes.c_int32 * 2)(16, 16)
+    good = (ctypes.c_float * 2)(2.0 ** -10, 2.0 ** -9)
+    bad = (ctypes.c_float * 2)(2.0 ** -10, 0.3)
+    a8 = lambda sk=good, sv=good, layout=None, weights=0x4000: lib.kvcomm_align_kv_q8(
+        ctypes.byref(m), 0, _tensor(), _tensor(0x5000), 16, parr, parr, layout or _tensor(None, st=128), larr, sk, sv, 2,
+        weights, 64, None, _tensor(0x6000), _tensor(0x7000), None)
+    assert a8(sk=bad) == EINVAL and a8(sv=bad) == EINVAL and a8(sk=None) == EINVAL
+    assert a8(layout=_tensor(None, st=24)) == EINVAL
+    assert a8(weights=None) == EINVAL
 
 
 def test_batch_argument_errors(lib):

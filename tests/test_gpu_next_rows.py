@@ -327,3 +327,102 @@ def test_batched_mixed_lengths_and_prefix_segment_update():
                               wo, delta, w.rope_theta, gran=oracle.GRAN_SEGMENT)
         check_close(f(out[0]), rk, w.dtype, "K^")
         check_close(f(out[1]), rv, w.dtype, "V^")
+
+
+# ------------------------------------------------------------------------- compressed deviations
+def test_e4m3_hardware_decode_is_the_ocp_format():
+    """All 256 codes through the kernel's unpacking (one anchor of weight 1 and scale 1, zero base, no
+    rotation, fp32 output) against the oracle's decoder: pins the conversion instruction's format."""
+    say("e4m3 decode")
+    w = scaled(SMALL_F32, n_layers=1, n_kv_heads=1, n_q_heads=1, head_dim=64, seg_len=4, n_anchors=1)
+    model = hotpath.model_of(w)
+    codes = torch.arange(256, dtype=torch.uint8, device=DEV).reshape(1, 1, 4, 64)
+    zero = torch.zeros((1, 1, 4, 64), dtype=torch.float32, device=DEV)
+    ones = torch.ones((4, 1), dtype=torch.float32, device=DEV)
+    ok, ov = torch.empty_like(zero), torch.empty_like(zero)
+    kv.kvcomm_align_kv_q8(model, zero, zero, [codes], [codes], [1.0], [2.0], ones, 0, ok, ov)
+    torch.cuda.synchronize()
+    want = np.array([oracle.e4m3_decode(c) for c in range(256)])
+    fin = ~np.isnan(want)
+    assert np.array_equal(ok.cpu().numpy().reshape(-1)[fin], want[fin].astype(np.float32))
+    assert np.array_equal(ov.cpu().numpy().reshape(-1)[fin], (2 * want[fin]).astype(np.float32))
+    assert np.isnan(ok.cpu().numpy().reshape(-1)[~fin]).all()
+
+
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32, scaled(SMALL_BF16, name="bf16_d64", head_dim=64, n_q_heads=2)],
+                         ids=lambda w: w.name)
+def test_quantize_deltas_bit_exact(w):
+    say(f"quantize {w.name}")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    x = seg.anchor_dk[0].clone()
+    x[0, 0, 0, :8] = torch.tensor([0.0, -0.0, 1e-9, 0.44, 10.0, -10.0, 2.0 ** -16, -2.0 ** -19], dtype=w.dtype)
+    # ties of the E4M3 grid that the model dtype can hold exactly (scale 2^-10): 1.0625, 1.1875, 2^-10, 3 * 2^-10
+    x[0, 0, 1, :4] = torch.tensor([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10], dtype=w.dtype) * 2.0 ** -10
+    for scale in (2.0 ** -10, 2.0 ** -7):
+        q = kv.kvcomm_quantize_deltas(model, x, scale)
+        torch.cuda.synchronize()
+        want = oracle.quantize(to_np(x), scale)
+        got = q.cpu().numpy()
+        # +0 and -0 are both zero: compare values, and codes wherever the value is not zero
+        same = got == want
+        zero_both = ((got & 0x7f) == 0) & ((want & 0x7f) == 0)
+        assert np.all(same | zero_both)
+    with pytest.raises(kv.KVCommError):
+        kv.kvcomm_quantize_deltas(model, x, 0.003)           # not a power of two
+
+
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32], ids=lambda w: w.name)
+@pytest.mark.parametrize("gran", [kv.W_TOKEN, kv.W_LAYER_HEAD_TOKEN, kv.W_SEGMENT])
+def test_align_with_compressed_deviations(w, gran):
+    say(f"align q8 {w.name} gran={gran}")
+    w = scaled(w, anchor_delta_choices=(16, 64, 100), n_anchors=6)
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    scales_k = [2.0 ** -10, 2.0 ** -9, 2.0 ** -10, 2.0 ** -11, 2.0 ** -10, 2.0 ** -8]
+    scales_v = [2.0 ** -10] * 6
+    qk = [kv.kvcomm_quantize_deltas(model, a, s) for a, s in zip(seg.anchor_dk, scales_k)]
+    qv = [kv.kvcomm_quantize_deltas(model, a, s) for a, s in zip(seg.anchor_dv, scales_v)]
+    wts, _, _ = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len, 1.0, gran)
+    ok, ov = torch.empty_like(seg.base_k), torch.empty_like(seg.base_v)
+    kv.kvcomm_align_kv_q8(model, seg.base_k, seg.base_v, qk, qv, scales_k, scales_v, wts, seg.delta_pos, ok, ov,
+                          seg.anchor_len, seg.anchor_delta_pos, gran)
+    torch.cuda.synchronize()
+    # the oracle sees what is stored: the decoded codes (its own quantiser of the same inputs gives the same codes)
+    dk = [oracle.dequantize(oracle.quantize(to_np(a), s), s) for a, s in zip(seg.anchor_dk, scales_k)]
+    dv = [oracle.dequantize(oracle.quantize(to_np(a), s), s) for a, s in zip(seg.anchor_dv, scales_v)]
+    bk, anc = oracle_inputs(seg)
+    dist, sel = oracle.distances(bk, anc, gran)
+    wo, _ = oracle.weights(dist, sel, 1.0)
+    rk, rv = oracle.align(bk, to_np(seg.base_v), dk, dv, wo, seg.delta_pos, w.rope_theta,
+                          anc_delta=seg.anchor_delta_pos, gran=gran)
+    check_close(to_np(ok), rk, w.dtype, "K^ q8")
+    check_close(to_np(ov), rv, w.dtype, "V^ q8")
+    # and the compression error itself stays within the format's bound: |dec - x| <= 2^-4 |x| (+ tiny absolute floor)
+    x = to_np(seg.anchor_dk[5])
+    assert np.all(np.abs(dk[5] - x) <= np.abs(x) * 2.0 ** -4 + scales_k[5] * 2.0 ** -10)
+
+
+def test_compressed_align_full_size_rate_inputs():
+    """Config-2 segment at full size through the compressed path, oracle on sampled tokens."""
+    w = scaled(workloads.LLAMA8B_5AGENTS, n_agents=1, n_segments=1)
+    say("align q8 full size")
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    s = 2.0 ** -10
+    qk = [kv.kvcomm_quantize_deltas(model, a, s) for a in seg.anchor_dk]
+    qv = [kv.kvcomm_quantize_deltas(model, a, s) for a in seg.anchor_dv]
+    wts, _, _ = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len)
+    ok, ov = torch.empty_like(seg.base_k), torch.empty_like(seg.base_v)
+    kv.kvcomm_align_kv_q8(model, seg.base_k, seg.base_v, qk, qv, [s] * 8, [s] * 8, wts, seg.delta_pos, ok, ov)
+    torch.cuda.synchronize()
+    tokens = [0, 31, 32, 255, 300, 511]
+    idx = torch.as_tensor(tokens, device=DEV)
+    f = lambda t: to_np(t[:, :, idx])
+    dk = [oracle.dequantize(oracle.quantize(f(a), s), s) for a in seg.anchor_dk]
+    dv = [oracle.dequantize(oracle.quantize(f(a), s), s) for a in seg.anchor_dv]
+    dist, sel = oracle.distances(f(seg.base_k), [f(a) for a in seg.anchor_k])
+    wo, _ = oracle.weights(dist, sel, 1.0)
+    rk, rv = oracle.align(f(seg.base_k), f(seg.base_v), dk, dv, wo, seg.delta_pos, w.rope_theta)
+    check_close(f(ok), rk, w.dtype, "K^ q8 full")
+    check_close(f(ov), rv, w.dtype, "V^ q8 full")
