@@ -316,3 +316,43 @@ def test_config4_long_context_sampled():
 
 def test_config5_llama70b_sampled():
     check_agent_sampled(workloads.LLAMA70B, 2, seg_ids=(3,), n_heads_checked=3, chain=False)
+
+
+def test_config2_batched_launch_as_benchmarked():
+    """Config 2 in the launch configuration the benchmark times: the four segments of an agent in one
+    batched launch per stage, then attention.  Oracle on sampled tokens of every segment (tokens are
+    independent under per-token weights) and on sampled (layer, query head) pairs of the attention, whose
+    reference cache is assembled by the oracle itself for those kv heads."""
+    w = workloads.LLAMA8B_5AGENTS
+    agent_id = 1
+    say(f"{w.name} agent {agent_id}, batched")
+    model = hotpath.model_of(w)
+    G = w.n_q_heads // w.n_kv_heads
+    agent = workloads.make_agent(w, agent_id, DEV)
+    pairs = [(0, 3), (17, 20), (31, 31)]
+    ocache = {(l, hq // G): (to_np(agent.cache_k[l, hq // G]), to_np(agent.cache_v[l, hq // G])) for l, hq in pairs}
+    sc = hotpath.align_agent_batched(w, model, agent)
+    out = kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx)
+    torch.cuda.synchronize()
+    for j, seg in enumerate(agent.segments):
+        p0, S = w.seg_offset(j), w.seg_len
+        tokens = sample_tokens(S, 100 + j)
+        ref = oracle_segment(w, seg, tokens)
+        idx = torch.as_tensor(tokens, device=DEV)
+        assert np.array_equal(sc.selected[j].cpu().numpy(), ref["selected"])
+        assert np.array_equal(sc.nearest[j].cpu().numpy()[tokens], ref["nearest"])
+        check_weights(sc.weights[j].cpu().numpy()[tokens], ref["w"].T)
+        check_close(to_np(agent.cache_k[:, :, p0:p0 + S][:, :, idx]), ref["out_k"], w.dtype, f"K^ seg {j}")
+        check_close(to_np(agent.cache_v[:, :, p0:p0 + S][:, :, idx]), ref["out_v"], w.dtype, f"V^ seg {j}")
+        # the oracle's own cache for the sampled kv heads: all tokens of the segment
+        dist, sel = oracle.distances(to_np(seg.base_k), [to_np(a) for a in seg.anchor_k])
+        wts, _ = oracle.weights(dist, sel, w.temperature)
+        for (l, hk), (ck, cv) in ocache.items():
+            cut = lambda t: to_np(t[l:l + 1, hk:hk + 1])
+            rk, rv = oracle.align(cut(seg.base_k), cut(seg.base_v), [cut(a) for a in seg.anchor_dk],
+                                  [cut(a) for a in seg.anchor_dv], wts, seg.delta_pos, w.rope_theta)
+            ck[p0:p0 + S], cv[p0:p0 + S] = rk[0, 0], rv[0, 0]
+    for (l, hq) in pairs:
+        ck, cv = ocache[(l, hq // G)]
+        want = oracle.suffix_attn(to_np(agent.q[l:l + 1, hq:hq + 1]), ck[None, None], cv[None, None], w.n_ctx)
+        check_close(to_np(out[l, hq]), want[0, 0], w.dtype, f"O[{l},{hq}]")
