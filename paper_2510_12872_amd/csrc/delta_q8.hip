@@ -17,6 +17,10 @@ namespace {
 
 using namespace kvc;
 
+#ifndef KVC_ALIGNQ8_BLOCKS
+#define KVC_ALIGNQ8_BLOCKS 2048   // blocks per tensor the grid of the compressed update aims at
+#endif
+
 constexpr int kBlock = 256;
 constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
 constexpr int kMaxHalf = 128;
@@ -34,6 +38,33 @@ __device__ __forceinline__ void unpack_q8(const uint32_t (&raw)[EPV / 4], float 
         out[4 * w + 2] = b[0];
         out[4 * w + 3] = b[1];
     }
+}
+
+// Deviation bytes of one anchor for this lane's channels of both halves, bf16 rows (8 channels per lane and
+// half = 8 bytes each).  Instead of two 8-byte loads per lane, the two lanes of a pair load 16 bytes each --
+// the even lane the pair's 16 channels of the first half, the odd lane those of the second half -- and
+// swap the halves they do not own with one DPP move per register (quad permutation 1,0,3,2): half as many
+// load instructions for the same bytes.  `row` points at the anchor's row, `pair_off` = 8 * (lane_in_row & ~1).
+struct Q8Pair {
+    u32x4 raw;   // as loaded
+};
+__device__ __forceinline__ Q8Pair load_q8_pair(const uint8_t *row, int pair_off, bool odd, int half_bytes)
+{
+    Q8Pair r;
+    r.raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + pair_off + (odd ? half_bytes : 0)));
+    return r;
+}
+__device__ __forceinline__ void split_q8_pair(const Q8Pair &r, bool odd, uint32_t (&lo)[2], uint32_t (&hi)[2])
+{
+    // even lane holds [lo_even, lo_odd], odd lane holds [hi_even, hi_odd] (8 bytes each)
+    const uint32_t s0 = odd ? r.raw[0] : r.raw[2];   // what the partner needs: even sends lo_odd, odd sends hi_even
+    const uint32_t s1 = odd ? r.raw[1] : r.raw[3];
+    const uint32_t g0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s0, 0xB1, 0xf, 0xf, true);
+    const uint32_t g1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s1, 0xB1, 0xf, 0xf, true);
+    lo[0] = odd ? g0 : r.raw[0];
+    lo[1] = odd ? g1 : r.raw[1];
+    hi[0] = odd ? r.raw[2] : g0;
+    hi[1] = odd ? r.raw[3] : g1;
 }
 
 template <int EPV>
@@ -203,25 +234,48 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
                 hi[e] += w * dhi[e];
             }
         };
-        // four anchors (eight independent loads) in flight
+        // four anchors in flight
         int a = 0;
-        for (; a + 4 <= p.n_sel; a += 4) {
-            uint32_t x[4][2][EPV / 4];
+        if constexpr (EPV == 8) {
+            // 16-byte loads shared by lane pairs (see load_q8_pair)
+            const bool odd = lir & 1;
+            const int64_t roff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token;
+            const int pair_off = 8 * (lir & ~1);
+            for (; a + 4 <= p.n_sel; a += 4) {
+                Q8Pair x[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint8_t *d = p.anc[which][a + u] + aoff;
-                load_q8<EPV>(d, x[u][0]);
-                load_q8<EPV>(d + HALF, x[u][1]);
+                for (int u = 0; u < 4; ++u) x[u] = load_q8_pair(p.anc[which][a + u] + roff, pair_off, odd, HALF);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    uint32_t x0[2], x1[2];
+                    split_q8_pair(x[u], odd, x0, x1);
+                    accumulate(a + u, x0, x1);
+                }
             }
+            for (; a < p.n_sel; ++a) {
+                uint32_t x0[2], x1[2];
+                split_q8_pair(load_q8_pair(p.anc[which][a] + roff, pair_off, odd, HALF), odd, x0, x1);
+                accumulate(a, x0, x1);
+            }
+        } else {
+            for (; a + 4 <= p.n_sel; a += 4) {
+                uint32_t x[4][2][EPV / 4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
-        }
-        for (; a < p.n_sel; ++a) {
-            uint32_t x0[EPV / 4], x1[EPV / 4];
-            const uint8_t *d = p.anc[which][a] + aoff;
-            load_q8<EPV>(d, x0);
-            load_q8<EPV>(d + HALF, x1);
-            accumulate(a, x0, x1);
+                for (int u = 0; u < 4; ++u) {
+                    const uint8_t *d = p.anc[which][a + u] + aoff;
+                    load_q8<EPV>(d, x[u][0]);
+                    load_q8<EPV>(d + HALF, x[u][1]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
+            }
+            for (; a < p.n_sel; ++a) {
+                uint32_t x0[EPV / 4], x1[EPV / 4];
+                const uint8_t *d = p.anc[which][a] + aoff;
+                load_q8<EPV>(d, x0);
+                load_q8<EPV>(d + HALF, x1);
+                accumulate(a, x0, x1);
+            }
         }
         T *yp = op + l * so.layer + h * so.head + t * so.token + col0;
         store16_stream(yp, pack<T>(lo));
@@ -360,7 +414,7 @@ extern "C" int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran, kvcom
     const int lpr = model->head_dim / (2 * (16 / es));
     const int rpb = kBlock / lpr;
     p.n_token_tiles = (seg_len + rpb - 1) / rpb;
-    int n_chunks = (32768 + p.n_token_tiles - 1) / p.n_token_tiles;
+    int n_chunks = (KVC_ALIGNQ8_BLOCKS + p.n_token_tiles - 1) / p.n_token_tiles;
     if (n_chunks > p.LH) n_chunks = p.LH;
     if (n_chunks < 1) n_chunks = 1;
     p.lh_per_block = (p.LH + n_chunks - 1) / n_chunks;
