@@ -34,18 +34,18 @@ HBM_TRAFFIC_BYTES = {"align_kv": 2416138240 + 268435456, "anchor_weights": 12081
 
 
 def cpu_baseline(w):
-    """Oracle (as it stands) on a bounded sample: four full segment alignments (all layers) plus the
-    suffix attention of one whole agent; scaled to the whole workload by segment / agent counts."""
+    """Oracle (as it stands) on a bounded sample: the eight segment alignments (all layers) and the suffix
+    attention of two whole agents; scaled to the whole workload by segment / agent counts."""
     import torch
 
     import oracle
     from paper_2510_12872_amd import workloads
 
     f64 = lambda t: t.to(torch.float64).numpy()
-    n_seg = 4
+    n_seg = 2 * w.n_segments                 # every segment of two agents
     t_align_sample = 0.0
     for j in range(n_seg):
-        seg = workloads.make_segment(w, 0, j, "cpu")
+        seg = workloads.make_segment(w, j // w.n_segments, j % w.n_segments, "cpu")
         args = (f64(seg.base_k), f64(seg.base_v), [f64(a) for a in seg.anchor_k],
                 [f64(a) for a in seg.anchor_dk], [f64(a) for a in seg.anchor_dv])
         t0 = time.perf_counter()
@@ -54,25 +54,77 @@ def cpu_baseline(w):
         del seg, args
     t_align = t_align_sample * (w.n_segments * w.n_agents / n_seg)
 
-    sl = w.n_layers                          # every layer and q head of one agent
-    wa = workloads.scaled(w, n_layers=sl, n_agents=1, n_segments=0, prefix_len=w.n_ctx)
-    ag = workloads.make_agent(wa, 0, "cpu")
-    q, k, v = f64(ag.q), f64(ag.cache_k), f64(ag.cache_v)
-    t0 = time.perf_counter()
-    oracle.suffix_attn(q, k, v, wa.n_ctx)
-    t_attn_sample = time.perf_counter() - t0
-    t_attn = t_attn_sample * (w.n_layers / sl) * w.n_agents
+    n_attn = 2                               # every layer and q head of two agents
+    wa = workloads.scaled(w, n_agents=n_attn, n_segments=0, prefix_len=w.n_ctx)
+    t_attn_sample = 0.0
+    for a in range(n_attn):
+        ag = workloads.make_agent(wa, a, "cpu")
+        q, k, v = f64(ag.q), f64(ag.cache_k), f64(ag.cache_v)
+        t0 = time.perf_counter()
+        oracle.suffix_attn(q, k, v, wa.n_ctx)
+        t_attn_sample += time.perf_counter() - t0
+        del ag, q, k, v
+    t_attn = t_attn_sample * (w.n_agents / n_attn)
     return {
         "value": w.aligned_tokens / (t_align + t_attn),
         "unit": "tokens/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
         "sample": (f"{n_seg} of {w.n_agents * w.n_segments} segment alignments, all layers ({t_align_sample:.2f} s) + "
-                   f"suffix attention of {sl} of {w.n_layers} layers of one agent ({t_attn_sample:.2f} s), "
-                   f"scaled by segment / layer / agent counts"),
+                   f"suffix attention of {n_attn} of {w.n_agents} agents, all layers ({t_attn_sample:.2f} s), "
+                   f"scaled by segment / agent counts"),
         "align_tokens_per_s": w.aligned_tokens / t_align,
         "attn_gflops": w.attn_flops() / t_attn / 1e9,
     }
+
+
+def mfma_calibration(torch, kv, w, model, dev):
+    """Matrix-core rate of a library GEMM and of the attention kernel, on N(0,1) inputs and on zeros.
+
+    The instruction streams are identical in both cases; only the operand bits differ, so the ratio shows what
+    the chip's power management costs on the benchmark's value distribution."""
+    from paper_2510_12872_amd import workloads
+
+    def time_ms(fn, warm, n):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    res = {}
+    n = 8192
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    a = torch.randn(n, n, generator=g, device=dev).to(torch.bfloat16)
+    b = torch.randn(n, n, generator=g, device=dev).to(torch.bfloat16)
+    for kind in ("normal", "zeros"):
+        if kind == "zeros":
+            a.zero_()
+            b.zero_()
+        ms = time_ms(lambda: torch.matmul(a, b.t()), 40, 60)
+        res[f"library_gemm_8192_{kind}_tflops"] = 2.0 * n ** 3 / ms / 1e9
+    del a, b
+    ag = workloads.make_agent(w, 0, dev, with_segments=False)
+    ag.cache_k[:, :, w.prefix_len:w.n_ctx] = torch.randn(ag.cache_k[:, :, w.prefix_len:w.n_ctx].shape, generator=g,
+                                                         device=dev).to(ag.cache_k.dtype)
+    ag.cache_v[:, :, w.prefix_len:w.n_ctx] = torch.randn(ag.cache_v[:, :, w.prefix_len:w.n_ctx].shape, generator=g,
+                                                         device=dev).to(ag.cache_v.dtype)
+    out = torch.empty_like(ag.q)
+    flops = workloads.scaled(w, n_agents=1).attn_flops()
+    for kind in ("normal", "zeros"):
+        if kind == "zeros":
+            ag.q.zero_()
+            ag.cache_k.zero_()
+            ag.cache_v.zero_()
+        ms = time_ms(lambda: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=out), 80, 60)
+        res[f"suffix_attn_{kind}_tflops"] = flops / ms / 1e9
+    return res
 
 
 def main():
@@ -86,6 +138,9 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference reading for HBM byte counters)")
+    ap.add_argument("--mfma-calibration", action="store_true",
+                    help="only time a library bf16 GEMM and the attention kernel on N(0,1) and on all-zero inputs "
+                         "(how far the data-dependent power limit moves the matrix-core rate on this box)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -111,6 +166,9 @@ def main():
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
+    if args.mfma_calibration:
+        print(json.dumps({"mfma_calibration": mfma_calibration(torch, kv, w, model, dev)}))
+        return
 
     agents = [workloads.make_agent(w, a, dev) for a in range(w.n_agents)]
     outs = [torch.empty_like(ag.q) for ag in agents]
