@@ -31,6 +31,7 @@
 // fp32 path (attn_f32_kernel): one wavefront per query row, plain fp32 FMA and expf with an
 // online softmax over 64-key chunks; it exists for exactness, not speed.
 #include <math.h>
+#include <type_traits>
 
 #include "kvcomm_device.h"
 
@@ -93,13 +94,24 @@ __device__ __forceinline__ void dma16(const unsigned char *src, const lds_byte *
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0) : "memory");
 }
 
-// The same with a wavefront-uniform 64-bit base (scalar registers) plus a per-lane 32-bit byte offset: the
-// steady-state loads then cost no vector ALU instruction (the row base advances on the scalar unit and
-// the per-lane offset never changes).
-__device__ __forceinline__ void dma16_sbase(const unsigned char *base, uint32_t voff, const lds_byte *dst)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
 {
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory");
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// The same with a wavefront-uniform 64-bit row base (scalar registers) plus a per-lane 32-bit byte offset,
+// and the LDS destination as a wavefront-uniform base plus a literal (M0 is formed by one scalar add):
+// the steady-state loads then cost no vector ALU instruction and no register per destination (the row
+// base advances on the scalar unit and the per-lane offset never changes).
+template <int OFF>
+__device__ __forceinline__ void dma16_sbase_at(const unsigned char *base, uint32_t voff, uint32_t dst_base)
+{
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 : : "v"(voff), "s"(base), "s"(dst_base), "n"(OFF) : "memory", "scc");
 }
 
 template <int D, int NW, int QB, int WPE>
@@ -204,9 +216,9 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
 
     // 64 keys starting at key0 (a multiple of 32) -> K ring; its two halves are h0 = key0/32 and h0+1.
     // A half outside [0, n_sub) is skipped.  The lower NW/2 wavefronts fill the first half, the rest the second.
-    // `clamp` (a literal at every call site) re-reads the last row for rows past the cache end; such
-    // rows are never unmasked.  Without it the caller guarantees that all 64 rows exist.
-    auto load_k64 = [&](int key0, bool clamp) __attribute__((always_inline)) {
+    // General form (prologue and the last tiles): rows past the cache end re-read the last row; such
+    // rows are never unmasked.
+    auto load_k64 = [&](int key0) __attribute__((always_inline)) {
         const int h = key0 / 32 + wave / (NW / 2);
         if (h < 0 || h >= n_sub) return;  // wavefront-uniform
         const int rbase = (wave % (NW / 2)) * RW;
@@ -214,18 +226,44 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 32 * h + rbase + it * RPL;  // wavefront-uniform
             const lds_byte *dst = kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB;
-            if (clamp) dma16(kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it), dst);
-            else dma16_sbase(kbytes + (int64_t)row0 * p.s_k.token * 2, ld_koff[it], dst);
+            dma16(kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it), dst);
         }
     };
-    auto load_v64 = [&](int tile, bool clamp) __attribute__((always_inline)) {
+    auto load_v64 = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int row0 = 64 * tile + wave * RW + it * RPL;
             const lds_byte *dst = vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB;
-            if (clamp) dma16(vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it), dst);
-            else dma16_sbase(vbytes + (int64_t)row0 * p.s_v.token * 2, ld_voff[it], dst);
+            dma16(vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it), dst);
         }
+    };
+    // Steady state (all rows exist, no half is skipped): the same loads from two running row pointers,
+    // so that a load costs one 64-bit scalar add instead of a 64-bit multiply, and with M0 formed from
+    // a per-wavefront LDS base plus a literal.  kp / vp point at this wavefront's next row to load.
+    const int64_t k_rpl = (int64_t)RPL * p.s_k.token * 2, v_rpl = (int64_t)RPL * p.s_v.token * 2;
+    const int64_t k_adv = (int64_t)(64 - LPT * RPL) * p.s_k.token * 2, v_adv = (int64_t)(64 - LPT * RPL) * p.s_v.token * 2;
+    const unsigned char *kp = kbytes + (int64_t)(96 + 32 * (wave / (NW / 2)) + (wave % (NW / 2)) * RW) * p.s_k.token * 2;
+    const unsigned char *vp = vbytes + (int64_t)(64 + wave * RW) * p.s_v.token * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)kring;
+    const uint32_t k_rows = lds0 + (wave % (NW / 2)) * RW * ROWB;
+    // K halves 2t+3, 2t+4 (t even) live in slots 3, 0; halves 2t+5, 2t+6 in slots 1, 2
+    const uint32_t kdst_a = __builtin_amdgcn_readfirstlane(k_rows + ((3 + wave / (NW / 2)) & 3) * HALFB);
+    const uint32_t kdst_b = __builtin_amdgcn_readfirstlane(k_rows + ((1 + wave / (NW / 2)) & 3) * HALFB);
+    const uint32_t vdst = __builtin_amdgcn_readfirstlane(lds0 + 4 * HALFB + wave * RW * ROWB);
+    auto load_kv_next = [&](uint32_t kdst, auto vb) __attribute__((always_inline)) {
+        constexpr int VB = decltype(vb)::value;  // V buffer, a literal
+        static_for<0, LPT>([&](auto it) __attribute__((always_inline)) {
+            constexpr int I = decltype(it)::value;
+            if (I > 0) kp += k_rpl;
+            dma16_sbase_at<I * RPL * ROWB>(kp, ld_koff[I], kdst);
+        });
+        kp += k_rpl + k_adv;
+        static_for<0, LPT>([&](auto it) __attribute__((always_inline)) {
+            constexpr int I = decltype(it)::value;
+            if (I > 0) vp += v_rpl;
+            dma16_sbase_at<VB * TILEB + I * RPL * ROWB>(vp, ld_voff[I], vdst);
+        });
+        vp += v_rpl + v_adv;
     };
 
     // ---- per-lane LDS read offsets
@@ -410,9 +448,9 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // ---- pipeline over tiles.  During tile t the sub-steps 2t and 2t+1 read K halves 2t+1 and 2t+2
     // and V tile t; the loads issued at its start (K halves 2t+3, 2t+4 into the slots of halves 2t-1
     // and 2t, V tile t+1 into the buffer of tile t-1) only overwrite what tile t-1 finished reading.
-    load_k64(-32, true);  // half 0
-    load_k64(32, true);   // halves 1, 2
-    load_v64(0, true);
+    load_k64(-32);  // half 0
+    load_k64(32);   // halves 1, 2
+    load_v64(0);
     tile_barrier();
 
     f32x16 s0[QB], s1[QB];
@@ -431,13 +469,21 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     }
     // Two tiles (four sub-steps) per trip so that ring slots and buffers are compile-time constants.
     auto tile_pair = [&](int t, bool clamp, bool masked) __attribute__((always_inline)) {
-        load_k64(64 * t + 96, clamp);
-        load_v64(t + 1, clamp);
+        if (clamp) {
+            load_k64(64 * t + 96);
+            load_v64(t + 1);
+        } else {
+            load_kv_next(kdst_a, std::integral_constant<int, 1>{});  // K halves 2t+3, 2t+4, V tile t+1
+        }
         substep(2 * t, 0, true, masked, s0, s1);
         substep(2 * t + 1, 1, true, masked, s1, s0);
         tile_barrier();
-        load_k64(64 * t + 160, clamp);
-        load_v64(t + 2, clamp);
+        if (clamp) {
+            load_k64(64 * t + 160);
+            load_v64(t + 2);
+        } else {
+            load_kv_next(kdst_b, std::integral_constant<int, 0>{});  // K halves 2t+5, 2t+6, V tile t+2
+        }
         substep(2 * t + 2, 2, true, masked, s0, s1);
         substep(2 * t + 3, 3, true, masked, s1, s0);
         tile_barrier();
@@ -446,8 +492,8 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     for (; t + 2 <= t_plain; t += 2) tile_pair(t, false, false);
     for (; t + 2 <= t_last; t += 2) tile_pair(t, true, true);
     if (t < t_last) {  // one more tile with a successor (t is even)
-        load_k64(64 * t + 96, true);
-        load_v64(t + 1, true);
+        load_k64(64 * t + 96);
+        load_v64(t + 1);
         substep(2 * t, 0, true, true, s0, s1);
         substep(2 * t + 1, 1, true, true, s1, s0);
         tile_barrier();
