@@ -51,7 +51,7 @@ struct AlignJob {
     int32_t S;                 // tokens
     int32_t w_pitch;           // anchors per weight row (n_anchors of the segment)
     int32_t n_token_tiles;
-    int32_t block0;            // first blockIdx.x of the segment
+    int32_t tile0;             // first of the segment's tiles in the launch-wide tile list
     int16_t a0, n_sel;         // its selected anchors: entries [a0, a0 + n_sel) of anc / col / tab
     int16_t t0, n_tab;         // its rotation tables: entries [t0, t0 + n_tab) of tab_delta
     int16_t base_tab;          // table of the base keys' rotation (index among the segment's tables) + 1, 0 = identity
@@ -64,6 +64,7 @@ struct AlignParams {
     int32_t H, LH;             // kv heads, layers*heads
     int32_t gran, n_jobs;
     int32_t lh_per_block;
+    int32_t tiles_total;       // token tiles of all segments
     int32_t tab_delta[kMaxTab];                 // position delta of each rotation table
     const void *anc[2][KVCOMM_MAX_ANCHORS];     // [0] dK, [1] dV of the selected anchors of all segments
     uint8_t col[KVCOMM_MAX_ANCHORS];            // weight column of a selected anchor
@@ -79,10 +80,14 @@ __global__ __launch_bounds__(kBlock, KVC_ALIGN_WPE) void align_kernel(const Alig
     constexpr int HALF = LPR * EPV;  // D / 2
     constexpr int RPB = kBlock / LPR;
 
+    // Block order: (layer, head) chunk, then segment, then token tile, so that the blocks in flight
+    // write neighbouring slices of the same cache rows when the segments of a launch are adjacent.
+    const int chunk = blockIdx.x / p.tiles_total;
+    const int r = blockIdx.x % p.tiles_total;
     int ji = 0;
 #pragma unroll
     for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
-        if (i < p.n_jobs && (int)blockIdx.x >= p.job[i].block0) ji = i;
+        if (i < p.n_jobs && r >= p.job[i].tile0) ji = i;
     const AlignJob &jb = p.job[ji];
     const int n_sel = jb.n_sel, a0 = jb.a0;
 
@@ -93,9 +98,7 @@ __global__ __launch_bounds__(kBlock, KVC_ALIGN_WPE) void align_kernel(const Alig
     const int tid = threadIdx.x;
     const int row = tid / LPR;
     const int lir = tid % LPR;
-    const int bx = blockIdx.x - jb.block0;
-    const int tile = bx % jb.n_token_tiles;
-    const int chunk = bx / jb.n_token_tiles;
+    const int tile = r - jb.tile0;
     const int which = blockIdx.y;          // 0 = keys (rotated), 1 = values
     const bool is_k = which == 0;
     const int t = tile * RPB + row;
@@ -320,11 +323,13 @@ extern "C" int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kv
     if (n_chunks < 1) n_chunks = 1;
     p.lh_per_block = (int32_t)((p.LH + n_chunks - 1) / n_chunks);
     n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
-    int64_t n_blocks = 0;
+    int32_t tile0 = 0;
     for (int j = 0; j < n_jobs; ++j) {
-        p.job[j].block0 = (int32_t)n_blocks;
-        n_blocks += n_chunks * p.job[j].n_token_tiles;
+        p.job[j].tile0 = tile0;
+        tile0 += p.job[j].n_token_tiles;
     }
+    p.tiles_total = (int32_t)tiles_total;
+    const int64_t n_blocks = n_chunks * tiles_total;
     if (n_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
