@@ -191,7 +191,9 @@ int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor
  *   workspace       kvcomm_suffix_attn_workspace() bytes (may be 0, then NULL is accepted).
  * bf16 tensors use bf16 MFMA with fp32 accumulation and an fp32 online softmax; f32 tensors
  * use fp32 arithmetic throughout.
- * Errors: KVCOMM_EINVAL for null/misaligned pointers, tq <= 0, n_ctx < 0.                */
+ * Errors: KVCOMM_EINVAL for null/misaligned pointers, tq <= 0, n_ctx < 0;
+ * KVCOMM_EUNSUPPORTED for bf16 caches whose token stride is D * 2^21 elements or more
+ * (the kernel addresses a group of 512 / D rows with a 32-bit byte offset).                 */
 size_t kvcomm_suffix_attn_workspace(const kvcomm_model *model, int32_t n_ctx, int32_t tq);
 
 int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q,

@@ -652,6 +652,13 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         return launch_status();
     }
 
+    // The direct loads address a row group as a 64-bit scalar base plus an unsigned 32-bit per-lane byte
+    // offset that spans up to 64 * 8 / D rows: the token stride has to leave that offset below 2^32.
+    if (D == 64 || D == 128 || D == 256) {
+        const int64_t rows_per_load = 64 * 8 / D;
+        const int64_t max_tok = ((int64_t)1 << 31) / (2 * rows_per_load);
+        if (cache_k.stride_token >= max_tok || cache_v.stride_token >= max_tok) return KVCOMM_EUNSUPPORTED;
+    }
     constexpr int NW = KVC_ATTN_NW;    // wavefronts per block
     constexpr int QB = KVC_ATTN_QB;    // 32-query blocks per wavefront
     constexpr int WPE = KVC_ATTN_WPE;  // wavefronts per SIMD the register budget is sized for

@@ -260,6 +260,13 @@ def test_suffix_attn_argument_errors(lib):
     assert call(out=_tensor(ptr=0x4004)) == EINVAL
     assert lib.kvcomm_suffix_attn(ctypes.byref(_model(n_q_heads=5)), _tensor(), _tensor(0x2000), _tensor(0x3000), 1, 1,
                                   0.0, _tensor(0x4000), None, None, 0, None) == EUNSUPPORTED
+    # a bf16 cache whose rows are too far apart for the kernel's 32-bit per-lane byte offsets
+    far = _tensor(0x2000)
+    far.stride_token = 1 << 28
+    far.stride_head = 1 << 40
+    far.stride_layer = 1 << 44
+    assert lib.kvcomm_suffix_attn(ctypes.byref(m), _tensor(), far, _tensor(0x3000), 10, 4, 0.0, _tensor(0x4000),
+                                  None, None, 0, None) == EUNSUPPORTED
 
 
 def test_binding_rejects_host_tensors_and_mixed_layouts(lib):
