@@ -81,17 +81,18 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds
 }
 
 // One wavefront-wide direct load global -> LDS (global_load_lds_dwordx4): lane i moves the 16 bytes at
-// its own global address `src` to LDS address `dst` + 16 * i (`dst` is wavefront-uniform and travels in M0).
+// global address `base` + `voff` (a wavefront-uniform 64-bit base in scalar registers plus its own unsigned
+// 32-bit byte offset) to LDS address `dst` + 16 * i (`dst` is wavefront-uniform and travels in M0).
 // Written as inline assembly on purpose: the compiler then does not know of the pending LDS write and
 // inserts no wait of its own before later LDS reads (it would wait for ALL outstanding loads ahead of the
 // first transposing read and so serialise the prefetch).  Ordering is explicit instead: tile_barrier()
 // waits for the loads (vmcnt) and synchronises the block before anybody reads what they wrote.
 // M0 is a reserved register that the compiler itself only ever sets immediately before an instruction
 // that consumes it, so overwriting it here disturbs nothing (nothing else in this file uses it).
-__device__ __forceinline__ void dma16(const unsigned char *src, const lds_byte *dst)
+__device__ __forceinline__ void dma16_sbase(const unsigned char *base, uint32_t voff, const lds_byte *dst)
 {
     const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(m0) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory");
 }
 
 template <int I, int N, class F>
@@ -103,10 +104,9 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-// The same with a wavefront-uniform 64-bit row base (scalar registers) plus a per-lane 32-bit byte offset,
-// and the LDS destination as a wavefront-uniform base plus a literal (M0 is formed by one scalar add):
-// the steady-state loads then cost no vector ALU instruction and no register per destination (the row
-// base advances on the scalar unit and the per-lane offset never changes).
+// The same with the LDS destination as a wavefront-uniform base plus a literal (M0 is formed by one scalar
+// add): the steady-state loads then cost no vector ALU instruction and no register per destination (the
+// row base advances on the scalar unit and the per-lane offset never changes).
 template <int OFF>
 __device__ __forceinline__ void dma16_sbase_at(const unsigned char *base, uint32_t voff, uint32_t dst_base)
 {
@@ -159,15 +159,13 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // This lane's query column in each of the wavefront's QB blocks: row r = i * G + g of the
     // (layer, kv head) group.
     int qi[QB], hq[QB];
-    bool qvalid[QB];
     bf16x8 qf[QB][NKS];
 #pragma unroll
     for (int b = 0; b < QB; ++b) {
         const int r_row = rt * BM + wave * MW + b * 32 + n;
-        qvalid[b] = r_row / p.G < p.tq;
         qi[b] = min(r_row / p.G, p.tq - 1);
         hq[b] = hkv * p.G + r_row % p.G;
-        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)hq[b] * p.s_q.head + qi[b] * p.s_q.token;
+        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)(uint32_t)hq[b] * p.s_q.head + (int64_t)(uint32_t)qi[b] * p.s_q.token;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) qf[b][ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
     }
@@ -217,25 +215,30 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // 64 keys starting at key0 (a multiple of 32) -> K ring; its two halves are h0 = key0/32 and h0+1.
     // A half outside [0, n_sub) is skipped.  The lower NW/2 wavefronts fill the first half, the rest the second.
     // General form (prologue and the last tiles): rows past the cache end re-read the last row; such
-    // rows are never unmasked.
+    // rows are never unmasked.  The row base is clamped on the scalar unit and a lane whose row would
+    // still fall behind the end steps its offset back by whole rows.
+    const int lq = lane / KCH;  // this lane's row inside a load
+    const uint32_t k_row_bytes = (uint32_t)(p.s_k.token * 2), v_row_bytes = (uint32_t)(p.s_v.token * 2);
+    auto load_rows = [&](const unsigned char *bytes, int64_t tok_stride, uint32_t row_bytes, int row0, uint32_t voff,
+                         const lds_byte *dst) __attribute__((always_inline)) {
+        const int row0c = min(row0, p.N - 1);            // wavefront-uniform
+        const int excess = max(lq - (p.N - 1 - row0c), 0);  // rows this lane would overshoot by
+        dma16_sbase(bytes + (int64_t)row0c * tok_stride * 2, voff - (uint32_t)excess * row_bytes, dst);
+    };
     auto load_k64 = [&](int key0) __attribute__((always_inline)) {
         const int h = key0 / 32 + wave / (NW / 2);
         if (h < 0 || h >= n_sub) return;  // wavefront-uniform
         const int rbase = (wave % (NW / 2)) * RW;
 #pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int row0 = 32 * h + rbase + it * RPL;  // wavefront-uniform
-            const lds_byte *dst = kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB;
-            dma16(kbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_k.token * 2 + in_row_k(it), dst);
-        }
+        for (int it = 0; it < LPT; ++it)
+            load_rows(kbytes, p.s_k.token, k_row_bytes, 32 * h + rbase + it * RPL, ld_koff[it],
+                      kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB);
     };
     auto load_v64 = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int row0 = 64 * tile + wave * RW + it * RPL;
-            const lds_byte *dst = vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB;
-            dma16(vbytes + (int64_t)min(row0 + lane / KCH, p.N - 1) * p.s_v.token * 2 + in_row_v(it), dst);
-        }
+        for (int it = 0; it < LPT; ++it)
+            load_rows(vbytes, p.s_v.token, v_row_bytes, 64 * tile + wave * RW + it * RPL, ld_voff[it],
+                      vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB);
     };
     // Steady state (all rows exist, no half is skipped): the same loads from two running row pointers,
     // so that a load costs one 64-bit scalar add instead of a 64-bit multiply, and with M0 formed from
@@ -513,9 +516,14 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum[b]), __float_as_uint(lsum[b]), false, false);
             ltot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
         }
-        if (!qvalid[b]) continue;
+        // Row coordinates again, from a freshly read lane id: the compiler then keeps none of the
+        // prologue's address terms alive across the tile loops (the register file is full there).
+        const int lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        const int r_row = rt * BM + wave * MW + b * 32 + (lane_e & 31);
+        if (r_row / p.G >= p.tq) continue;
+        const uint32_t qi_e = (uint32_t)(r_row / p.G), hq_e = (uint32_t)(hkv * p.G + r_row % p.G), hg_e = (uint32_t)lane_e >> 5;
         const float inv = 1.f / ltot;
-        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq[b] * p.s_o.head + qi[b] * p.s_o.token;
+        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq_e * p.s_o.head + (int64_t)qi_e * p.s_o.token;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -523,10 +531,10 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
                 u32x2 w;
                 w[0] = pack_bf16x2(o[b][db][4 * j4] * inv, o[b][db][4 * j4 + 1] * inv);
                 w[1] = pack_bf16x2(o[b][db][4 * j4 + 2] * inv, o[b][db][4 * j4 + 3] * inv);
-                *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg) = w;
+                *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg_e) = w;
             }
-        if (p.lse && hg == 0)
-            p.lse[((int64_t)l * p.Hkv * p.G + hq[b]) * p.tq + qi[b]] = m[b] * p.scale + logf(ltot);
+        if (p.lse && hg_e == 0)
+            p.lse[((int64_t)l * p.Hkv * p.G + hq_e) * p.tq + qi_e] = m[b] * p.scale + logf(ltot);
     }
 }
 
