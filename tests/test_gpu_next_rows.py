@@ -426,3 +426,61 @@ def test_compressed_align_full_size_rate_inputs():
     rk, rv = oracle.align(f(seg.base_k), f(seg.base_v), dk, dv, wo, seg.delta_pos, w.rope_theta)
     check_close(f(ok), rk, w.dtype, "K^ q8 full")
     check_close(f(ov), rv, w.dtype, "V^ q8 full")
+
+
+def test_whole_step_under_hip_graph_capture_and_replay():
+    """The library only enqueues kernels (no allocation, copy or memset), so a caller can record a whole
+    reuse step of an agent into a HIP graph.  Every replay, with eager work and synchronisations between
+    the replays and inputs changed in place, must reproduce the eager result bit for bit."""
+    w = scaled(workloads.LLAMA8B_5AGENTS, name="graph", n_layers=4, n_kv_heads=2, n_q_heads=8, n_agents=1,
+               prefix_len=64, seg_len=200, n_segments=3, n_anchors=6, tq=40, anchor_delta_choices=(64, 264))
+    say("graph capture")
+    model = hotpath.model_of(w)
+    agent = workloads.make_agent(w, 0, DEV)
+    sc = hotpath.AgentScratch(model, [w.seg_len] * w.n_segments, [w.n_anchors] * w.n_segments, kv.W_TOKEN, DEV)
+    out = torch.empty_like(agent.q)
+    lse = torch.empty(agent.q.shape[:3], dtype=torch.float32, device=DEV)
+
+    def step():
+        hotpath.align_agent_batched(w, model, agent, kv.W_TOKEN, sc)
+        kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx, out=out, lse_out=lse)
+
+    def eager_reference():
+        step()
+        torch.cuda.synchronize()
+        return agent.cache_k.clone(), agent.cache_v.clone(), out.clone(), lse.clone(), [x.clone() for x in sc.weights]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7)
+    for replay in range(3):
+        # new inputs in the same buffers: the graph holds addresses, not values
+        seg = agent.segments[replay % w.n_segments]
+        seg.base_k.copy_(torch.randn(seg.base_k.shape, generator=g, device=DEV).to(seg.base_k.dtype))
+        agent.q.copy_(torch.randn(agent.q.shape, generator=g, device=DEV).to(agent.q.dtype))
+        want = eager_reference()
+        for t in (agent.cache_k[:, :, w.prefix_len:w.n_ctx], agent.cache_v[:, :, w.prefix_len:w.n_ctx], out, lse):
+            t.zero_()                            # eager work between the replays; stale results cannot pass
+        for x in sc.weights:
+            x.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (agent.cache_k, agent.cache_v, out, lse, sc.weights)
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1]), f"replay {replay}: caches differ"
+        assert torch.equal(got[2], want[2]) and torch.equal(got[3], want[3]), f"replay {replay}: attention differs"
+        for a, b in zip(got[4], want[4]):
+            assert torch.equal(a, b), f"replay {replay}: weights differ"
+    # and the last replay against the oracle, end to end, on one (layer, head) sample of the attention output
+    q, k, v = (to_np(t) for t in (agent.q, agent.cache_k, agent.cache_v))
+    check_close(to_np(out[:1]), oracle.suffix_attn(q[:1], k[:1], v[:1], w.n_ctx), w.dtype, "graph replay attention")
