@@ -89,9 +89,12 @@ SMALL_BF16 = scaled(workloads.LLAMA8B_5AGENTS, name="small_bf16", n_layers=3, n_
 SMALL_F32_D128 = scaled(workloads.TINY, name="small_f32_d128", head_dim=128, seg_len=77, prefix_len=5, tq=19,
                         n_anchors=3)
 SMALL_BF16_D64 = scaled(SMALL_BF16, name="small_bf16_d64", head_dim=64, n_q_heads=2, seg_len=131)
+SMALL_BF16_D256 = scaled(SMALL_BF16, name="small_bf16_d256", head_dim=256, n_layers=2, n_q_heads=4, seg_len=90, tq=45)
+SMALL_F32_D256 = scaled(workloads.TINY, name="small_f32_d256", head_dim=256, seg_len=40, prefix_len=3, tq=9, n_anchors=2)
 
 
-@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32_D128, SMALL_BF16_D64], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL_BF16, SMALL_F32_D128, SMALL_BF16_D64, SMALL_BF16_D256, SMALL_F32_D256],
+                         ids=lambda w: w.name)
 def test_small_whole_hot_path(w):
     say(f"small whole path {w.name}")
     model = hotpath.model_of(w)
