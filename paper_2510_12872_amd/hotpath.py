@@ -37,6 +37,21 @@ def align_segment(model, seg, out_k, out_v, temperature=1.0, gran=kv.W_TOKEN, sc
     return scratch
 
 
+def launch_chunks(n_anchors):
+    """Cut the segments of an agent (given by their anchor counts) into launches: one launch carries at
+    most MAX_BATCH segments and MAX_ANCHORS anchors over all of them."""
+    chunks, cur, n_anc = [], [], 0
+    for j, a in enumerate(n_anchors):
+        if cur and (len(cur) == kv.MAX_BATCH or n_anc + a > kv.MAX_ANCHORS):
+            chunks.append(cur)
+            cur, n_anc = [], 0
+        cur.append(j)
+        n_anc += a
+    if cur:
+        chunks.append(cur)
+    return chunks
+
+
 class AgentScratch:
     """Reusable device buffers for the batched weight step of all segments of one agent."""
 
@@ -47,19 +62,20 @@ class AgentScratch:
             self.weights.append(torch.empty((n, A), dtype=torch.float32, device=device))
             self.nearest.append(torch.empty((n,), dtype=torch.int32, device=device))
             self.selected.append(torch.empty((A,), dtype=torch.int32, device=device))
-        need = kv.kvcomm_anchor_weights_batch_workspace(model, seg_lens, n_anchors, gran, rule)
+        seg_lens, n_anchors = list(seg_lens), list(n_anchors)
+        need = max(kv.kvcomm_anchor_weights_batch_workspace(model, [seg_lens[j] for j in c], [n_anchors[j] for j in c],
+                                                            gran, rule) for c in launch_chunks(n_anchors))
         self.workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=device)
 
 
 def align_agent_batched(w, model, agent, gran=kv.W_TOKEN, scratch=None, stream=None):
-    """Anchor weights, then aligned K/V of ALL segments of an agent: one batched call per step
-    (chunks of binding.MAX_BATCH segments)."""
+    """Anchor weights, then aligned K/V of ALL segments of an agent: one batched call per step and
+    chunk of segments (a launch holds at most MAX_BATCH segments and MAX_ANCHORS anchors)."""
     segs = agent.segments
     if scratch is None:
         scratch = AgentScratch(model, [s.base_k.shape[2] for s in segs], [len(s.anchor_k) for s in segs], gran,
                                segs[0].base_k.device)
-    for c0 in range(0, len(segs), kv.MAX_BATCH):
-        idx = range(c0, min(c0 + kv.MAX_BATCH, len(segs)))
+    for idx in launch_chunks([len(s.anchor_k) for s in segs]):
         kv.kvcomm_anchor_weights_batch(model, [dict(
             seg_base_k=segs[j].base_k, anchor_base_k=segs[j].anchor_k, anchor_len=segs[j].anchor_len,
             weights_out=scratch.weights[j], nearest_out=scratch.nearest[j], selected_out=scratch.selected[j])

@@ -278,3 +278,16 @@ def test_binding_rejects_host_tensors_and_mixed_layouts(lib):
         binding._desc(x, torch.bfloat16, "x")
     with pytest.raises(kv.KVCommError):
         kv.Model(2, 2, 4, 128, torch.float16, 5e5).c()
+
+
+def test_launch_chunks_respect_segment_and_anchor_limits():
+    from paper_2510_12872_amd import hotpath
+    assert hotpath.launch_chunks([8, 8, 8, 8]) == [[0, 1, 2, 3]]
+    assert hotpath.launch_chunks([3] * 11) == [list(range(8)), [8, 9, 10]]
+    assert hotpath.launch_chunks([30, 30, 30]) == [[0, 1], [2]]
+    assert hotpath.launch_chunks([64, 1, 63, 64]) == [[0], [1, 2], [3]]
+    assert hotpath.launch_chunks([]) == []
+    for counts in ([5, 60, 4, 4, 64, 1, 1, 1, 1, 1, 1, 1, 1, 1], [16] * 9):
+        chunks = hotpath.launch_chunks(counts)
+        assert [j for c in chunks for j in c] == list(range(len(counts)))
+        assert all(len(c) <= kv.MAX_BATCH and sum(counts[j] for j in c) <= kv.MAX_ANCHORS for c in chunks)

@@ -484,3 +484,27 @@ def test_whole_step_under_hip_graph_capture_and_replay():
     # and the last replay against the oracle, end to end, on one (layer, head) sample of the attention output
     q, k, v = (to_np(t) for t in (agent.q, agent.cache_k, agent.cache_v))
     check_close(to_np(out[:1]), oracle.suffix_attn(q[:1], k[:1], v[:1], w.n_ctx), w.dtype, "graph replay attention")
+
+
+def test_batched_agent_is_cut_into_launches_by_segment_and_anchor_limits():
+    """Eleven segments (more than one launch holds) and, separately, pools whose anchors add up to more
+    than one launch holds: the helper cuts the agent into several launches; result as per-segment calls."""
+    for name, n_segments, n_anchors in (("many segments", 11, 3), ("many anchors", 3, 30)):
+        w = scaled(workloads.LLAMA8B_5AGENTS, name="cut", n_layers=2, n_kv_heads=2, n_q_heads=4, n_agents=1,
+                   prefix_len=8, seg_len=40, n_segments=n_segments, n_anchors=n_anchors, tq=4)
+        say(f"batched agent, {name}")
+        model = hotpath.model_of(w)
+        agent = workloads.make_agent(w, 0, DEV)
+        ref_k, ref_v = agent.cache_k.clone(), agent.cache_v.clone()
+        singles = []
+        for j, seg in enumerate(agent.segments):
+            p0 = w.seg_offset(j)
+            singles.append(hotpath.align_segment(model, seg, ref_k[:, :, p0:p0 + w.seg_len], ref_v[:, :, p0:p0 + w.seg_len]))
+        sc = hotpath.align_agent_batched(w, model, agent)
+        torch.cuda.synchronize()
+        for j in range(w.n_segments):
+            assert torch.equal(sc.nearest[j], singles[j].nearest)
+            assert float((sc.weights[j] - singles[j].weights).abs().max()) < 1e-6
+        err_k = float((agent.cache_k.float() - ref_k.float()).abs().max())
+        err_v = float((agent.cache_v.float() - ref_v.float()).abs().max())
+        assert err_k < 2e-2 and err_v < 2e-2, (err_k, err_v)   # same path up to the last bit of the weights
