@@ -472,6 +472,9 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         for (int c = 0; c < 4; ++c) max_chunk(b, 0, true, s0[b], mx, c, 4);
         (void)max_finish(b, mx);
     }
+    // Half 0 has no tile before it: every wavefront must have read it before the loads of the first
+    // tile pair (half 4 shares its slot) are issued.
+    __syncthreads();
     // Two tiles (four sub-steps) per trip so that ring slots and buffers are compile-time constants.
     auto tile_pair = [&](int t, bool clamp, bool masked) __attribute__((always_inline)) {
         if (clamp) {
