@@ -127,6 +127,74 @@ def mfma_calibration(torch, kv, w, model, dev):
     return res
 
 
+def next_rows(torch, kv, w, model, dev):
+    """Each entry point beyond the reuse step proper, timed alone on one 512-token segment of the workload:
+    30 launches over three rotating input sets (nothing stays in the last-level cache), HIP events."""
+    from paper_2510_12872_amd import workloads
+
+    segs = [workloads.make_segment(w, 0, j, dev) for j in range(3)]
+    A, S = w.n_anchors, w.seg_len
+    rows = w.n_layers * w.n_kv_heads * S
+    rb = w.head_dim * 2                                           # bytes per bf16 row
+    scale = 2.0 ** -10
+    outs = [(torch.empty_like(sg.base_k), torch.empty_like(sg.base_v)) for sg in segs]
+    out2 = [(torch.empty_like(sg.base_k), torch.empty_like(sg.base_v)) for sg in segs]
+    q8 = [([kv.kvcomm_quantize_deltas(model, a, scale) for a in sg.anchor_dk],
+           [kv.kvcomm_quantize_deltas(model, a, scale) for a in sg.anchor_dv]) for sg in segs]
+    n_slots = kv.kvcomm_weight_slots(model, S, kv.W_TOKEN)
+    wts = torch.empty((n_slots, A), dtype=torch.float32, device=dev)
+    nearest = torch.empty((n_slots,), dtype=torch.int32, device=dev)
+    selected = torch.empty((A,), dtype=torch.int32, device=dev)
+    ws = torch.empty((max(kv.kvcomm_anchor_weights_rule_workspace(model, S, A, kv.W_TOKEN, kv.RULE_COSINE_SOFTMAX),
+                          kv.kvcomm_anchor_weights_rule_workspace(model, S, A, kv.W_TOKEN, kv.RULE_NEAREST), 256),),
+                     dtype=torch.uint8, device=dev)
+    pws = torch.empty((max(kv.kvcomm_anchor_predict_workspace(n_slots), 256),), dtype=torch.uint8, device=dev)
+    pres = torch.empty((2,), dtype=torch.float32, device=dev)
+
+    def rule(r):
+        return lambda i: kv.kvcomm_anchor_weights_rule(model, r, segs[i % 3].base_k, segs[i % 3].anchor_k,
+                                                       segs[i % 3].anchor_len, w.temperature, kv.W_TOKEN, wts, nearest,
+                                                       selected, ws)
+
+    def capture(i):
+        sg = segs[i % 3]                                           # the next segment's base cache stands in for a real one
+        o = segs[(i + 1) % 3]
+        kv.kvcomm_capture_offsets(model, sg.base_k, sg.base_v, o.base_k, o.base_v, sg.delta_pos, outs[i % 3][0], outs[i % 3][1])
+
+    def quantize(i):
+        kv.kvcomm_quantize_deltas(model, segs[i % 3].anchor_dk[i % A], scale, q8[i % 3][0][i % A])
+
+    def align_q8(i):
+        sg, (qk, qv), o = segs[i % 3], q8[i % 3], out2[i % 3]
+        kv.kvcomm_align_kv_q8(model, sg.base_k, sg.base_v, qk, qv, [scale] * A, [scale] * A, wts, sg.delta_pos, o[0], o[1],
+                              sg.anchor_len, sg.anchor_delta_pos)
+
+    def predict(i):
+        kv.kvcomm_anchor_predict(wts, segs[0].anchor_len, S, 0.3, result_out=pres, workspace=pws)
+
+    cases = (("anchor_weights_rule nearest", rule(kv.RULE_NEAREST), rows * rb * (A + 1)),
+             ("anchor_weights_rule cosine", rule(kv.RULE_COSINE_SOFTMAX), rows * rb * (A + 1)),
+             ("capture_offsets", capture, rows * rb * 6),
+             ("quantize_deltas", quantize, rows * w.head_dim * 3),
+             ("align_kv_q8", align_q8, rows * w.head_dim * (4 * 2 + 2 * A)),
+             ("anchor_predict", predict, n_slots * A * 4))
+    res = {}
+    for label, fn, nbytes in cases:
+        for i in range(6):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(30):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 30
+        res[label] = {"avg_call_us": ms * 1e3, "algorithmic_bytes": nbytes, "achieved_GBps": nbytes / ms / 1e6,
+                      "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +209,9 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="two streams: weights + align of agent i+1 run beside the attention of agent i "
                          "(per-kernel figures then come from a sequential pass before the timed region)")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="only time the entry points beyond the reuse step proper (weighting variants, offset "
+                         "capture, anchor prediction, 8-bit deviations) on one segment of the workload")
     ap.add_argument("--mfma-calibration", action="store_true",
                     help="only time a library bf16 GEMM and the attention kernel on N(0,1) and on all-zero inputs "
                          "(how far the data-dependent power limit moves the matrix-core rate on this box)")
@@ -171,6 +242,10 @@ def main():
     model = hotpath.model_of(w)
     if args.mfma_calibration:
         print(json.dumps({"mfma_calibration": mfma_calibration(torch, kv, w, model, dev)}))
+        return
+    if args.next_rows:
+        print(json.dumps({"next_rows": next_rows(torch, kv, w, model, dev), "workload": w.name,
+                          "unit": "one 512-token segment, all layers and kv heads"}))
         return
 
     agents = [workloads.make_agent(w, a, dev) for a in range(w.n_agents)]
