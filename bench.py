@@ -117,6 +117,15 @@ def mfma_calibration(torch, kv, w, model, dev):
                                                          device=dev).to(ag.cache_v.dtype)
     out = torch.empty_like(ag.q)
     flops = workloads.scaled(w, n_agents=1).attn_flops()
+    # torch's own fused attention on the same tensors (grouped heads, every query sees the whole cache: a little
+    # more work than the causal suffix attention) as a second reference for what this machine sustains
+    import torch.nn.functional as F
+    sdpa_flops = 4.0 * w.head_dim * w.n_q_heads * w.n_layers * w.tq * (w.n_ctx + w.tq)
+    try:
+        ms = time_ms(lambda: F.scaled_dot_product_attention(ag.q, ag.cache_k, ag.cache_v, enable_gqa=True), 20, 30)
+        res["torch_sdpa_full_mask_normal_tflops"] = sdpa_flops / ms / 1e9
+    except Exception as exc:  # an older torch without grouped heads: the reference is optional
+        res["torch_sdpa_full_mask_normal_tflops"] = f"unavailable ({type(exc).__name__})"
     for kind in ("normal", "zeros"):
         if kind == "zeros":
             ag.q.zero_()
