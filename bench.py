@@ -215,6 +215,9 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference reading for HBM byte counters)")
+    ap.add_argument("--hbm-calibration", action="store_true",
+                    help="only time torch's device copy and a read-only reduction over 2 GiB (what plain library "
+                         "kernels sustain from HBM on this box)")
     ap.add_argument("--overlap", action="store_true",
                     help="two streams: weights + align of agent i+1 run beside the attention of agent i "
                          "(per-kernel figures then come from a sequential pass before the timed region)")
@@ -246,6 +249,24 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4,
                                                "launches": 5}}))
+        return
+    if args.hbm_calibration:
+        src = torch.ones(1 << 29, dtype=torch.float32, device=dev)   # 2 GiB: far beyond the 256 MB last-level cache
+        dst = torch.empty_like(src)
+        res = {}
+        for label, fn, nbytes in (("copy_1_to_1", lambda: dst.copy_(src), 2 * src.numel() * 4),
+                                  ("read_only_sum", lambda: torch.sum(src), src.numel() * 4)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[label + "_GBps"] = nbytes / (e0.elapsed_time(e1) / 20) / 1e6
+        print(json.dumps({"hbm_calibration": res, "peak_GBps": HBM_PEAK_GBS}))
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
