@@ -204,6 +204,66 @@ def next_rows(torch, kv, w, model, dev):
     return res
 
 
+def per_config(torch, kv, dev):
+    """Every baseline configuration's kernels timed alone: one segment (anchor weights, then align into
+    contiguous outputs) over rotating input sets, and the suffix attention of one agent; HIP events."""
+    from paper_2510_12872_amd import hotpath, workloads
+
+    def time_ms(fn, warm, n):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    res = {}
+    for name in ("llama8b_5agents", "pool_scaling_a4", "pool_scaling_a16", "pool_scaling_a32", "pool_scaling_a64",
+                 "long_context", "llama70b"):
+        w = workloads.WORKLOADS[name]
+        model = hotpath.model_of(w)
+        one = workloads.scaled(w, n_agents=1, n_segments=1)
+        sets = 3 if one.align_bytes() < (8 << 30) else 2           # nothing stays in the 256 MB last-level cache
+        segs = [workloads.make_segment(w, 0, j, dev) for j in range(sets)]
+        outs = [(torch.empty_like(sg.base_k), torch.empty_like(sg.base_v)) for sg in segs]
+        sc = hotpath.Scratch(model, w.seg_len, w.n_anchors, kv.W_TOKEN, dev)
+
+        def run_w(i):
+            sg = segs[i % sets]
+            kv.kvcomm_anchor_weights(model, sg.base_k, sg.anchor_k, sg.anchor_len, w.temperature, kv.W_TOKEN, sc.weights,
+                                     sc.nearest, sc.selected, sc.workspace)
+
+        def run_a(i):
+            sg, o = segs[i % sets], outs[i % sets]
+            kv.kvcomm_align_kv(model, sg.base_k, sg.base_v, sg.anchor_dk, sg.anchor_dv, sc.weights, sg.delta_pos, o[0], o[1],
+                               sg.anchor_len, sg.anchor_delta_pos)
+
+        t_w, t_a = time_ms(run_w, sets, 30), time_ms(run_a, sets, 30)
+        r = {"segment": f"S {w.seg_len}, A {w.n_anchors}, L {w.n_layers}",
+             "weights_us": t_w * 1e3, "weights_frac_hbm": one.distance_bytes() / t_w / 1e6 / HBM_PEAK_GBS,
+             "align_us": t_a * 1e3, "align_frac_hbm": one.align_bytes() / t_a / 1e6 / HBM_PEAK_GBS}
+        del segs, outs, sc
+        if w.tq > 0:
+            ag = workloads.make_agent(w, 0, dev, with_segments=False)
+            g = torch.Generator(device=dev)
+            g.manual_seed(1)
+            for c in (ag.cache_k, ag.cache_v):                       # the slots the alignment would fill
+                c[:, :, w.prefix_len:w.n_ctx] = torch.randn(c[:, :, w.prefix_len:w.n_ctx].shape, generator=g,
+                                                            device=dev).to(c.dtype)
+            out = torch.empty_like(ag.q)
+            t_t = time_ms(lambda i: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=out), 80, 40)
+            fl = workloads.scaled(w, n_agents=1).attn_flops()
+            r.update({"attn_ms": t_t, "attn_tflops": fl / t_t / 1e9, "attn_frac_mfma": fl / t_t / 1e9 / MFMA_BF16_PEAK_TFLOPS})
+            del ag, out
+        res[name] = r
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -218,6 +278,8 @@ def main():
     ap.add_argument("--hbm-calibration", action="store_true",
                     help="only time torch's device copy and a read-only reduction over 2 GiB (what plain library "
                          "kernels sustain from HBM on this box)")
+    ap.add_argument("--per-config", action="store_true",
+                    help="only time the kernels of every baseline configuration alone (one segment / one agent)")
     ap.add_argument("--overlap", action="store_true",
                     help="two streams: weights + align of agent i+1 run beside the attention of agent i "
                          "(per-kernel figures then come from a sequential pass before the timed region)")
@@ -267,6 +329,9 @@ def main():
             torch.cuda.synchronize()
             res[label + "_GBps"] = nbytes / (e0.elapsed_time(e1) / 20) / 1e6
         print(json.dumps({"hbm_calibration": res, "peak_GBps": HBM_PEAK_GBS}))
+        return
+    if args.per_config:
+        print(json.dumps({"per_config": per_config(torch, kv, dev)}))
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
