@@ -291,3 +291,14 @@ def test_launch_chunks_respect_segment_and_anchor_limits():
         chunks = hotpath.launch_chunks(counts)
         assert [j for c in chunks for j in c] == list(range(len(counts)))
         assert all(len(c) <= kv.MAX_BATCH and sum(counts[j] for j in c) <= kv.MAX_ANCHORS for c in chunks)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark runs on one GPU only; asking for more exits with a message (and never touches a device)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
