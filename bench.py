@@ -273,6 +273,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
+    ap.add_argument("--no-overlap-info", action="store_true",
+                    help="skip the two-stream steps that follow the timed region (profiling runs: every launch of "
+                         "the trace then ran alone on the chip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference reading for HBM byte counters)")
     ap.add_argument("--hbm-calibration", action="store_true",
@@ -421,7 +424,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     overlap_ms = None
-    if not args.overlap:
+    if not args.overlap and not args.no_overlap_info:
         # For information, after the timed region: the same steps with the next agent's alignment beside the
         # attention of the current one (two streams).  `value` and the rooflines above do not use it.
         n_ov = max(1, min(args.steps, 10))
@@ -493,7 +496,7 @@ def main():
     }
     if args.overlap:
         result["overlap"] = "two streams; roofline / kernels from a sequential pass before the timed region"
-    else:
+    elif overlap_ms is not None:
         result["two_stream_overlap"] = {"ms_per_step": overlap_ms, "tokens_per_s": w.aligned_tokens / (overlap_ms * 1e-3),
                                         "note": "same steps, next agent's alignment beside attention; not used for value"}
     if not args.no_cpu_baseline:
