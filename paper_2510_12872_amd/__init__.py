@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     kvcomm_align_kv, kvcomm_align_kv_batch, kvcomm_align_kv_q8, kvcomm_anchor_predict, kvcomm_anchor_predict_workspace, kvcomm_anchor_weights,
     kvcomm_anchor_weights_batch, kvcomm_anchor_weights_batch_workspace,
     kvcomm_anchor_weights_rule, kvcomm_anchor_weights_rule_workspace, kvcomm_anchor_weights_workspace,
-    kvcomm_capture_offsets, kvcomm_quantize_deltas, kvcomm_suffix_attn, kvcomm_weight_slots, library_path, load_library,
+    kvcomm_capture_offsets, kvcomm_quantize_deltas, kvcomm_suffix_attn, kvcomm_suffix_attn_workspace, kvcomm_weight_slots, library_path,
+    load_library,
 )

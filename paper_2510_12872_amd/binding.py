@@ -241,6 +241,10 @@ def kvcomm_align_kv(model, base_k, base_v, anchor_dk, anchor_dv, weights, delta_
     return out_k, out_v
 
 
+def kvcomm_suffix_attn_workspace(model, n_ctx, tq):
+    return int(load_library().kvcomm_suffix_attn_workspace(ctypes.byref(model.c()), int(n_ctx), int(tq)))
+
+
 def kvcomm_suffix_attn(model, q, cache_k, cache_v, n_ctx, softmax_scale=0.0, out=None, lse_out=None,
                        want_lse=False, stream=None):
     """Causal attention of the suffix queries q [L,Hq,Tq,D] over cache_k/v [L,Hkv,n_ctx+Tq,D]."""

@@ -28,7 +28,7 @@ def lib():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(kvcomm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(kvcomm_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(lib):
@@ -41,6 +41,14 @@ def test_header_symbols_are_exported(lib):
     assert lib.kvcomm_version() >= 120
     for st in (0, -1, -2, -3, -4, 17):
         assert lib.kvcomm_status_string(st)
+
+
+def test_every_entry_point_has_a_binding_of_the_same_name():
+    """The Python layer is a thin binding: one function per C entry point, same name."""
+    for n in declared_functions():
+        if n in ("kvcomm_status_string", "kvcomm_version"):
+            continue                      # used through load_library() / KVCommError
+        assert callable(getattr(kv, n, None)), f"{n} has no binding of the same name"
 
 
 def test_header_is_plain_c(tmp_path):
