@@ -123,6 +123,13 @@ def test_cosine_special_cases():
     np.testing.assert_allclose(simr, sim, atol=1e-12)
     w2, _ = oracle.weights_from_sim(sim, sel, tau=1e-4)
     np.testing.assert_allclose(w2[0], 1.0, atol=1e-12)
+    # exactly equal similarities: equal weights, and the most similar anchor is the one of lowest index
+    tied = np.array([[0.25, 0.9], [0.75, 0.9], [0.75, 0.1], [0.75, 0.9]])
+    wt, bt = oracle.weights_from_sim(tied, np.array([1, 1, 1, 1], dtype=np.int32), tau=0.5)
+    assert bt.tolist() == [1, 0]
+    assert wt[1, 0] == wt[2, 0] == wt[3, 0] and wt[0, 1] == wt[1, 1] == wt[3, 1]
+    wt, bt = oracle.weights_from_sim(tied, np.array([1, 0, 1, 1], dtype=np.int32), tau=0.5)
+    assert bt.tolist() == [2, 0] and np.all(wt[1] == 0)
 
 
 def test_nearest_is_argmin_one_hot_and_limit_of_softmax():
