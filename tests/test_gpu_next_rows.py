@@ -96,6 +96,15 @@ def test_rules_with_duplicate_and_identical_anchors():
     dist, sel = oracle.distances(bk, anc)
     _, near = oracle.weights_nearest(dist, sel)
     assert np.array_equal(nn.cpu().numpy(), near) and set(near.tolist()) <= {0, 1}
+    # the same ties under the cosine rule: equal weights, lowest index is the most similar anchor
+    wc, nc, _ = kv.kvcomm_anchor_weights_rule(model, kv.RULE_COSINE_SOFTMAX, seg.base_k, seg.anchor_k, seg.anchor_len,
+                                              0.2)
+    torch.cuda.synchronize()
+    sim, sel_c = oracle.cosine(bk, anc)
+    want, best = oracle.weights_from_sim(sim, sel_c, 0.2)
+    assert np.array_equal(nc.cpu().numpy(), best) and set(best.tolist()) <= {0, 1}
+    assert torch.equal(wc[:, 0], wc[:, 3]) and torch.equal(wc[:, 1], wc[:, 2])
+    check_weights(wc.cpu().numpy(), want.T, "cosine weights with ties")
 
 
 def test_nearest_rule_feeds_align():
