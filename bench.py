@@ -181,12 +181,31 @@ def next_rows(torch, kv, w, model, dev):
     def predict(i):
         kv.kvcomm_anchor_predict(wts, segs[0].anchor_len, S, 0.3, result_out=pres, workspace=pws)
 
+    # the per-(layer, head, token) reading of the distance: one softmax per row instead of per token
+    n_lh = kv.kvcomm_weight_slots(model, S, kv.W_LAYER_HEAD_TOKEN)
+    wts_lh = torch.empty((n_lh, A), dtype=torch.float32, device=dev)
+    near_lh = torch.empty((n_lh,), dtype=torch.int32, device=dev)
+    ws_lh = torch.empty((max(kv.kvcomm_anchor_weights_workspace(model, S, A, kv.W_LAYER_HEAD_TOKEN), 256),),
+                        dtype=torch.uint8, device=dev)
+
+    def weights_lh(i):
+        sg = segs[i % 3]
+        kv.kvcomm_anchor_weights(model, sg.base_k, sg.anchor_k, sg.anchor_len, w.temperature, kv.W_LAYER_HEAD_TOKEN,
+                                 wts_lh, near_lh, selected, ws_lh)
+
+    def align_lh(i):
+        sg, o = segs[i % 3], out2[i % 3]
+        kv.kvcomm_align_kv(model, sg.base_k, sg.base_v, sg.anchor_dk, sg.anchor_dv, wts_lh, sg.delta_pos, o[0], o[1],
+                           sg.anchor_len, sg.anchor_delta_pos, kv.W_LAYER_HEAD_TOKEN)
+
     cases = (("anchor_weights_rule nearest", rule(kv.RULE_NEAREST), rows * rb * (A + 1)),
              ("anchor_weights_rule cosine", rule(kv.RULE_COSINE_SOFTMAX), rows * rb * (A + 1)),
              ("capture_offsets", capture, rows * rb * 6),
              ("quantize_deltas", quantize, rows * w.head_dim * 3),
              ("align_kv_q8", align_q8, rows * w.head_dim * (4 * 2 + 2 * A)),
-             ("anchor_predict", predict, n_slots * A * 4))
+             ("anchor_predict", predict, n_slots * A * 4),
+             ("anchor_weights per (layer, head, token)", weights_lh, rows * rb * (A + 1)),
+             ("align_kv per (layer, head, token)", align_lh, rows * rb * 2 * (A + 2)))
     res = {}
     for label, fn, nbytes in cases:
         for i in range(6):
