@@ -70,14 +70,24 @@ struct DistJob {
     int64_t comp_stride;   // elements between components (cosine rule)
     int32_t S, n_token_tiles, block0;
     int16_t a0, n_sel;     // its selected anchors: entries [a0, a0 + n_sel) of anc
+    // outputs of the fused form (per-(layer, head, token) weights straight from the distance kernel)
+    float *weights;
+    int32_t *nearest;
+    int32_t *selected_out;
+    uint64_t sel_mask;     // bit a = anchor a is selected
+    int32_t n_anchors;
 };
 
 struct DistParams {
     DistJob job[KVCOMM_MAX_BATCH];
     Strides s_anc;
     int32_t H, LH, lh_per_block, n_jobs;
+    int32_t fused, rule;   // fused: a row's distances are complete inside its lanes; write the weights here
+    double tau;
     const void *anc[KVCOMM_MAX_ANCHORS];  // selected anchors of all segments
+    uint8_t col[KVCOMM_MAX_ANCHORS];      // original index of a selected anchor
 };
+static_assert(sizeof(DistParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 __device__ __forceinline__ int job_of_block(const DistParams &p)
 {
@@ -148,9 +158,63 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
             double v = acc[j];
 #pragma unroll
             for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
-            if (valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
+            acc[j] = v;  // every lane of the row now holds the row's sum
+            if (!p.fused && valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
         }
     }
+    if (!p.fused) return;
+
+    // Fused form (one (layer, head) per block, all selected anchors in this anchor tile): the softmax of
+    // the row runs here.  Lane r of the row takes anchors r, r + LPR, ...; maxima, arg-max (lowest index
+    // among equals) and the denominator are joined by fixed butterflies, so all lanes agree bit for bit.
+    constexpr int NPL = (kAnchorTile + LPR - 1) / LPR;  // anchors per lane
+    if (bx == 0 && jb.selected_out && tid < jb.n_anchors) jb.selected_out[tid] = (int32_t)((jb.sel_mask >> tid) & 1);
+    double sc[NPL];
+    double smax = -INFINITY;
+    int best = kAnchorTile;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        const int a = lir + k * LPR;
+        double v = 0.0;
+#pragma unroll
+        for (int j = 0; j < kAnchorTile; ++j) v = j == a ? acc[j] : v;
+        sc[k] = a < na ? -sqrt(v) : -INFINITY;
+        if (sc[k] > smax) {  // ascending a: the lowest index wins among equals
+            smax = sc[k];
+            best = a;
+        }
+    }
+#pragma unroll
+    for (int off = LPR / 2; off >= 1; off >>= 1) {
+        const double om = __shfl_xor(smax, off, LPR);
+        const int ob = __shfl_xor(best, off, LPR);
+        if (om > smax || (om == smax && ob < best)) {
+            smax = om;
+            best = ob;
+        }
+    }
+    // The exponent is formed in double (distances of a few hundred differ by fractions); the exponential
+    // and the normalisation are fp32, which is what the fp32 weights can resolve.
+    float e[NPL], denom = 0.f;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        const int a = lir + k * LPR;
+        e[k] = a < na ? (p.rule == KVCOMM_RULE_NEAREST ? (a == best ? 1.f : 0.f) : expf((float)((sc[k] - smax) / p.tau))) : 0.f;
+        denom += e[k];
+    }
+#pragma unroll
+    for (int off = LPR / 2; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, LPR);
+    if (!valid) return;
+    const int64_t slot = (int64_t)chunk * jb.S + t;
+    float *wrow = jb.weights + slot * jb.n_anchors;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        const int a = lir + k * LPR;
+        if (a < na) wrow[p.col[jb.a0 + a]] = e[k] / denom;
+    }
+    for (int c = lir; c < jb.n_anchors; c += LPR)
+        if (!((jb.sel_mask >> c) & 1)) wrow[c] = 0.f;
+    if (lir == 0 && jb.nearest) jb.nearest[slot] = p.col[jb.a0 + best];
 }
 
 constexpr int kCosTile = 8;  // anchors per lane in the cosine variant (two accumulators each)
@@ -475,7 +539,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
     const bool cosine = rule == KVCOMM_RULE_COSINE_SOFTMAX;
     DistParams dp{};
     FinalParams fp{};
-    int n_sel_total = 0, max_sel = 0;
+    int n_sel_total = 0, max_sel = 0, min_sel = KVCOMM_MAX_ANCHORS;
     size_t need = 0;
     for (int j = 0; j < n_jobs; ++j) {
         const kvcomm_weights_job &jd = jobs[j];
@@ -488,7 +552,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
             if (jd.anchor_len[a] < jd.seg_len) continue;
             if (!jd.anchor_base_k[a] || !aligned16(jd.anchor_base_k[a])) return KVCOMM_EINVAL;
             if (n_sel_total + n_sel >= KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;  // over all segments of the launch
-            fp.col[n_sel_total + n_sel] = (uint8_t)a;
+            fp.col[n_sel_total + n_sel] = dp.col[n_sel_total + n_sel] = (uint8_t)a;
             fj.sel_mask |= (uint64_t)1 << a;
             dp.anc[n_sel_total + n_sel] = jd.anchor_base_k[a];
             ++n_sel;
@@ -496,6 +560,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
         dj.n_sel = fj.n_sel = (int16_t)n_sel;
         n_sel_total += n_sel;
         max_sel = n_sel > max_sel ? n_sel : max_sel;
+        min_sel = n_sel < min_sel ? n_sel : min_sel;
         need += n_jobs == 1 ? job_partial_bytes(pl, jd.seg_len, jd.n_anchors, rule)
                             : align256(job_partial_bytes(pl, jd.seg_len, jd.n_anchors, rule));
     }
@@ -507,6 +572,13 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
     dp.LH = model->n_layers * model->n_kv_heads;
     dp.lh_per_block = pl.lh_per_block;
     dp.n_jobs = n_jobs;
+    // One softmax per (layer, head, token): a row's distances are complete inside the lanes that read the
+    // row, so the distance kernel writes the weights itself (no partial sums, no second kernel) as long as
+    // every segment's selected anchors fit one anchor tile.
+    const bool fused = gran == KVCOMM_W_LAYER_HEAD_TOKEN && !cosine && min_sel >= 1 && max_sel <= kAnchorTile;
+    dp.fused = fused ? 1 : 0;
+    dp.rule = rule;
+    dp.tau = (double)temperature;
     fp.n_chunks = pl.n_chunks;
     fp.gran = gran;
     fp.rule = rule;
@@ -528,6 +600,11 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
         dj.block0 = (int32_t)dist_blocks;
         dist_blocks += (int64_t)pl.n_chunks * dj.n_token_tiles;
 
+        dj.weights = jd.weights_out;
+        dj.nearest = jd.nearest_out;
+        dj.selected_out = jd.selected_out;
+        dj.sel_mask = fj.sel_mask;
+        dj.n_anchors = jd.n_anchors;
         fj.partial = dj.partial;
         fj.weights = jd.weights_out;
         fj.nearest = jd.nearest_out;
@@ -564,6 +641,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
         }
         if (st) return st;
     }
+    if (fused) return KVCOMM_OK;
     if (gran == KVCOMM_W_SEGMENT)
         hipLaunchKernelGGL(finalize_segment_kernel, dim3(n_jobs), dim3(kBlock), 0, s, fp);
     else
