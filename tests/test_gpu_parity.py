@@ -359,3 +359,14 @@ def test_config2_batched_launch_as_benchmarked():
         ck, cv = ocache[(l, hq // G)]
         want = oracle.suffix_attn(to_np(agent.q[l:l + 1, hq:hq + 1]), ck[None, None], cv[None, None], w.n_ctx)
         check_close(to_np(out[l, hq]), want[0, 0], w.dtype, f"O[{l},{hq}]")
+
+
+@pytest.mark.parametrize("n_anchors,lens", [(5, None), (16, None), (17, None), (4, (1, 2, 3, 4)), (18, (60,) * 9 + (3,) * 9)])
+def test_layer_head_token_weights_fused_and_two_stage(n_anchors, lens):
+    """One softmax per (layer, head, token): the distance kernel finishes the softmax itself for pools of up to 16
+    selected anchors and falls back to the two-stage form otherwise (larger pools, nothing selected)."""
+    w = scaled(SMALL_BF16, n_anchors=n_anchors, seg_len=45, n_layers=2, anchor_lens=lens)
+    say(f"layer-head-token weights A={n_anchors} lens={lens}")
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    sc, ok, ov = run_segment(w, seg, kv.W_LAYER_HEAD_TOKEN)
+    compare_segment(w, seg, sc, ok, ov, kv.W_LAYER_HEAD_TOKEN)
