@@ -158,63 +158,113 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
             double v = acc[j];
 #pragma unroll
             for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
-            acc[j] = v;  // every lane of the row now holds the row's sum
-            if (!p.fused && valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
+            if (valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
         }
     }
-    if (!p.fused) return;
+}
 
-    // Fused form (one (layer, head) per block, all selected anchors in this anchor tile): the softmax of
-    // the row runs here.  Lane r of the row takes anchors r, r + LPR, ...; maxima, arg-max (lowest index
-    // among equals) and the denominator are joined by fixed butterflies, so all lanes agree bit for bit.
+// One softmax per (layer, head, token), pools of up to kAnchorTile selected anchors: a row's distances are
+// complete inside the LPR lanes that read the row, so this kernel finishes the softmax itself and writes the
+// weights (no partial sums, no second kernel).
+// Lane r of a row takes anchors r, r + LPR, ...; maximum, arg-max (lowest index among equals) and denominator
+// are joined by fixed butterflies, so all lanes of a row agree bit for bit.  The exponent is formed in double
+// (distances of a few hundred differ by fractions); the exponential and the normalisation are fp32, which is
+// what the fp32 weights can resolve.
+template <typename T, int LPR>
+__global__ __launch_bounds__(kBlock) void dist_row_softmax_kernel(const DistParams p)
+{
+    constexpr int EPV = Elem<T>::EPV;
+    constexpr int RPB = kBlock / LPR;
     constexpr int NPL = (kAnchorTile + LPR - 1) / LPR;  // anchors per lane
+    const DistJob &jb = p.job[job_of_block(p)];
+    const int tid = threadIdx.x;
+    const int row = tid / LPR, lir = tid % LPR;
+    const int bx = blockIdx.x - jb.block0;
+    const int tile = bx % jb.n_token_tiles;
+    const int chunk = bx / jb.n_token_tiles;
+    const int na = jb.n_sel;  // 1 ... kAnchorTile (checked by the host)
+    const int t = tile * RPB + row;
+    const bool valid = t < jb.S;
+    const int lh0 = chunk * p.lh_per_block;
+    const int lh1 = min(lh0 + p.lh_per_block, p.LH);
     if (bx == 0 && jb.selected_out && tid < jb.n_anchors) jb.selected_out[tid] = (int32_t)((jb.sel_mask >> tid) & 1);
-    double sc[NPL];
-    double smax = -INFINITY;
-    int best = kAnchorTile;
+
+    const T *seg = static_cast<const T *>(jb.seg_k);
+    for (int lh = lh0; lh < lh1; ++lh) {
+        double acc[kAnchorTile];
 #pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-        const int a = lir + k * LPR;
-        double v = 0.0;
+        for (int j = 0; j < kAnchorTile; ++j) acc[j] = 0.0;
+        if (valid) {
+            const int l = lh / p.H, h = lh % p.H;
+            const u32x4 rs = load16_stream(seg + l * jb.s_seg.layer + h * jb.s_seg.head + t * jb.s_seg.token + lir * EPV);
+            const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + lir * EPV;
+            u32x4 ra[kAnchorTile];
 #pragma unroll
-        for (int j = 0; j < kAnchorTile; ++j) v = j == a ? acc[j] : v;
-        sc[k] = a < na ? -sqrt(v) : -INFINITY;
-        if (sc[k] > smax) {  // ascending a: the lowest index wins among equals
-            smax = sc[k];
-            best = a;
+            for (int j = 0; j < kAnchorTile; ++j)
+                if (j < na) ra[j] = load16_stream(static_cast<const T *>(p.anc[jb.a0 + j]) + aoff);
+            float x[EPV];
+            unpack<T>(rs, x);
+#pragma unroll
+            for (int j = 0; j < kAnchorTile; ++j)
+                if (j < na) sqdiff_acc<T>(acc[j], x, ra[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kAnchorTile; ++j) {
+            if (j < na) {
+                double v = acc[j];
+#pragma unroll
+                for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
+                acc[j] = v;  // every lane of the row now holds the row's sum
+            }
+        }
+        double sc[NPL];
+        double smax = -INFINITY;
+        int best = kAnchorTile;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            const int a = lir + k * LPR;
+            double v = 0.0;
+#pragma unroll
+            for (int j = 0; j < kAnchorTile; ++j) v = j == a ? acc[j] : v;
+            sc[k] = a < na ? -sqrt(v) : -INFINITY;
+            if (sc[k] > smax) {  // ascending a: the lowest index wins among equals
+                smax = sc[k];
+                best = a;
+            }
+        }
+#pragma unroll
+        for (int off = LPR / 2; off >= 1; off >>= 1) {
+            const double om = __shfl_xor(smax, off, LPR);
+            const int ob = __shfl_xor(best, off, LPR);
+            if (om > smax || (om == smax && ob < best)) {
+                smax = om;
+                best = ob;
+            }
+        }
+        float e[NPL], denom = 0.f;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            const int a = lir + k * LPR;
+            e[k] = a < na ? (p.rule == KVCOMM_RULE_NEAREST ? (a == best ? 1.f : 0.f)
+                                                           : expf((float)((sc[k] - smax) / p.tau)))
+                          : 0.f;
+            denom += e[k];
+        }
+#pragma unroll
+        for (int off = LPR / 2; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, LPR);
+        if (valid) {
+            const int64_t slot = (int64_t)lh * jb.S + t;
+            float *wrow = jb.weights + slot * jb.n_anchors;
+#pragma unroll
+            for (int k = 0; k < NPL; ++k) {
+                const int a = lir + k * LPR;
+                if (a < na) wrow[p.col[jb.a0 + a]] = e[k] / denom;
+            }
+            for (int c = lir; c < jb.n_anchors; c += LPR)
+                if (!((jb.sel_mask >> c) & 1)) wrow[c] = 0.f;
+            if (lir == 0 && jb.nearest) jb.nearest[slot] = p.col[jb.a0 + best];
         }
     }
-#pragma unroll
-    for (int off = LPR / 2; off >= 1; off >>= 1) {
-        const double om = __shfl_xor(smax, off, LPR);
-        const int ob = __shfl_xor(best, off, LPR);
-        if (om > smax || (om == smax && ob < best)) {
-            smax = om;
-            best = ob;
-        }
-    }
-    // The exponent is formed in double (distances of a few hundred differ by fractions); the exponential
-    // and the normalisation are fp32, which is what the fp32 weights can resolve.
-    float e[NPL], denom = 0.f;
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-        const int a = lir + k * LPR;
-        e[k] = a < na ? (p.rule == KVCOMM_RULE_NEAREST ? (a == best ? 1.f : 0.f) : expf((float)((sc[k] - smax) / p.tau))) : 0.f;
-        denom += e[k];
-    }
-#pragma unroll
-    for (int off = LPR / 2; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, LPR);
-    if (!valid) return;
-    const int64_t slot = (int64_t)chunk * jb.S + t;
-    float *wrow = jb.weights + slot * jb.n_anchors;
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-        const int a = lir + k * LPR;
-        if (a < na) wrow[p.col[jb.a0 + a]] = e[k] / denom;
-    }
-    for (int c = lir; c < jb.n_anchors; c += LPR)
-        if (!((jb.sel_mask >> c) & 1)) wrow[c] = 0.f;
-    if (lir == 0 && jb.nearest) jb.nearest[slot] = p.col[jb.a0 + best];
 }
 
 constexpr int kCosTile = 8;  // anchors per lane in the cosine variant (two accumulators each)
@@ -446,6 +496,10 @@ __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalPar
 template <typename T, int LPR>
 int launch_dist(const DistParams &p, int n_blocks, int max_sel, bool cosine, hipStream_t stream)
 {
+    if (p.fused) {
+        hipLaunchKernelGGL((dist_row_softmax_kernel<T, LPR>), dim3(n_blocks), dim3(kBlock), 0, stream, p);
+        return launch_status();
+    }
     if (cosine) {
         const int a_tiles = (max_sel + kCosTile - 1) / kCosTile;
         hipLaunchKernelGGL((cos_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
@@ -576,6 +630,8 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
     // row, so the distance kernel writes the weights itself (no partial sums, no second kernel) as long as
     // every segment's selected anchors fit one anchor tile.
     const bool fused = gran == KVCOMM_W_LAYER_HEAD_TOKEN && !cosine && min_sel >= 1 && max_sel <= kAnchorTile;
+    // (one (layer, head) pair per block, as in the two-stage form: with runs of several pairs per block the
+    // softmax of one pair delays the loads of the next, measured 6 % slower)
     dp.fused = fused ? 1 : 0;
     dp.rule = rule;
     dp.tau = (double)temperature;
