@@ -139,8 +139,11 @@ int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float tempera
  *                      deviation is added unrotated (rotate the base key, then add the offset).
  *   out_k, out_v       [L, Hkv, seg_len, D] destination, normally a view into the agent's
  *                      cache at the segment's token offset (so concatenation costs nothing).
- *                      May be exactly the base tensors (in place); partial overlap is not
- *                      allowed and is not detected.
+ *                      out_k may be exactly base_k, and out_v exactly base_v (in place: same
+ *                      pointer and strides).  Any other sharing of bytes between an output and
+ *                      another tensor of the call (the other output, a base tensor, a selected
+ *                      anchor's deviations, the weights) returns KVCOMM_EINVAL; the check works
+ *                      on the byte runs of whole (layer, head) blocks, first to last token.
  * n_anchors may be 0 (pure re-positioning; weights may then be NULL).
  * Errors: KVCOMM_EINVAL / KVCOMM_EUNSUPPORTED as above.                                  */
 int kvcomm_align_kv(const kvcomm_model *model, int32_t gran,
@@ -156,11 +159,14 @@ int kvcomm_align_kv(const kvcomm_model *model, int32_t gran,
  * independently and "in parallel").  Job j has exactly the arguments of kvcomm_align_kv; all
  * jobs share `anchor_layout` and the weight granularity.  For a prefix segment pass its own
  * base cache and stored deviations with the PLACEHOLDER's weights: per-segment weights
- * (KVCOMM_W_SEGMENT) apply to a segment of any length, per-token weights need equal lengths.
+ * (KVCOMM_W_SEGMENT) apply to a segment of any length, per-token weights need equal lengths:
+ * each job states the rows of its weight buffer (weights_slots), and a job whose rows differ from
+ * kvcomm_weight_slots(seg_len, gran) is refused with KVCOMM_EINVAL before anything is read.
  * Limits: n_jobs <= KVCOMM_MAX_BATCH; over all jobs at most KVCOMM_MAX_ANCHORS selected anchors
  * and KVCOMM_MAX_ANCHORS + 1 distinct rotations; beyond them KVCOMM_EUNSUPPORTED (split the call).
- * Results are bit-identical to n_jobs separate kvcomm_align_kv calls.  Outputs of different
- * jobs must not overlap.                                                                  */
+ * Results are bit-identical to n_jobs separate kvcomm_align_kv calls.  The aliasing rule of
+ * kvcomm_align_kv holds across jobs too: an output that shares bytes with another job's output
+ * or inputs returns KVCOMM_EINVAL.                                                        */
 typedef struct {
     kvcomm_tensor base_k, base_v;       /* [L, Hkv, seg_len, D] */
     kvcomm_tensor out_k, out_v;
@@ -171,7 +177,8 @@ typedef struct {
     const int32_t *anchor_len;          /* HOST [n_anchors] */
     const int32_t *anchor_delta_pos;    /* HOST [n_anchors] or NULL */
     int32_t n_anchors;
-    const float *weights;               /* DEVICE [n, n_anchors] */
+    const float *weights;               /* DEVICE [weights_slots, n_anchors] */
+    int64_t weights_slots;              /* rows of `weights`; must equal kvcomm_weight_slots(seg_len, gran) */
 } kvcomm_align_job;
 
 int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
@@ -300,8 +307,9 @@ int kvcomm_capture_offsets(const kvcomm_model *model, kvcomm_tensor base_k, kvco
  * strides multiples of 16.
  *
  * kvcomm_quantize_deltas: in [L, Hkv, n_tokens, D] of the model dtype -> out, same shape, E4M3
- * bytes of in / scale rounded to nearest (ties to even).  scale must be a power of two
- * (else KVCOMM_EINVAL): the division is then exact and the codes are reproducible bit for bit.
+ * bytes of in / scale rounded to nearest (ties to even); a NaN becomes the code 0x7f, +-infinity
+ * saturates like any value beyond +-448 * scale.  scale must be a normal power of two, 2^-126 ...
+ * 2^127 (else KVCOMM_EINVAL): the division is then exact and the codes are reproducible bit for bit.
  *
  * kvcomm_align_kv_q8: kvcomm_align_kv with anchor_dk / anchor_dv pointing at E4M3 tensors laid
  * out by `anchor_layout` (bytes) and HOST arrays anchor_scale_k / anchor_scale_v [n_anchors] of
@@ -317,6 +325,29 @@ int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran,
                        const float *anchor_scale_k, const float *anchor_scale_v, int32_t n_anchors,
                        const float *weights, int32_t delta_pos, const int32_t *anchor_delta_pos,
                        kvcomm_tensor out_k, kvcomm_tensor out_v, void *stream);
+
+/* The compressed update for several segments in ONE launch: kvcomm_align_kv_batch with E4M3
+ * deviations.  Job j has the per-segment arguments of kvcomm_align_kv_q8; limits, aliasing rule
+ * and the weights_slots check are those of kvcomm_align_kv_batch; results are bit-identical to
+ * n_jobs separate kvcomm_align_kv_q8 calls.                                                   */
+typedef struct {
+    kvcomm_tensor base_k, base_v;       /* [L, Hkv, seg_len, D], model dtype */
+    kvcomm_tensor out_k, out_v;
+    int32_t seg_len;
+    int32_t delta_pos;
+    const void *const *anchor_dk;       /* HOST [n_anchors] of DEVICE pointers to E4M3 tensors */
+    const void *const *anchor_dv;
+    const int32_t *anchor_len;          /* HOST [n_anchors] */
+    const int32_t *anchor_delta_pos;    /* HOST [n_anchors] or NULL */
+    const float *anchor_scale_k;        /* HOST [n_anchors], powers of two */
+    const float *anchor_scale_v;
+    int32_t n_anchors;
+    const float *weights;               /* DEVICE [weights_slots, n_anchors] */
+    int64_t weights_slots;
+} kvcomm_align_q8_job;
+
+int kvcomm_align_kv_q8_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
+                             const kvcomm_align_q8_job *jobs, int32_t n_jobs, void *stream);
 
 /* Human-readable name of a kvcomm_status; never NULL. */
 const char *kvcomm_status_string(int status);

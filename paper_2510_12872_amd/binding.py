@@ -48,7 +48,16 @@ class _CAlignJob(ctypes.Structure):
                 ("seg_len", ctypes.c_int32), ("delta_pos", ctypes.c_int32),
                 ("anchor_dk", ctypes.POINTER(ctypes.c_void_p)), ("anchor_dv", ctypes.POINTER(ctypes.c_void_p)),
                 ("anchor_len", ctypes.POINTER(ctypes.c_int32)), ("anchor_delta_pos", ctypes.POINTER(ctypes.c_int32)),
-                ("n_anchors", ctypes.c_int32), ("weights", ctypes.c_void_p)]
+                ("n_anchors", ctypes.c_int32), ("weights", ctypes.c_void_p), ("weights_slots", ctypes.c_int64)]
+
+
+class _CAlignQ8Job(ctypes.Structure):
+    _fields_ = [("base_k", _CTensor), ("base_v", _CTensor), ("out_k", _CTensor), ("out_v", _CTensor),
+                ("seg_len", ctypes.c_int32), ("delta_pos", ctypes.c_int32),
+                ("anchor_dk", ctypes.POINTER(ctypes.c_void_p)), ("anchor_dv", ctypes.POINTER(ctypes.c_void_p)),
+                ("anchor_len", ctypes.POINTER(ctypes.c_int32)), ("anchor_delta_pos", ctypes.POINTER(ctypes.c_int32)),
+                ("anchor_scale_k", ctypes.POINTER(ctypes.c_float)), ("anchor_scale_v", ctypes.POINTER(ctypes.c_float)),
+                ("n_anchors", ctypes.c_int32), ("weights", ctypes.c_void_p), ("weights_slots", ctypes.c_int64)]
 
 
 class _CWeightsJob(ctypes.Structure):
@@ -133,6 +142,8 @@ def load_library():
                                        _CTensor, ctypes.POINTER(i32), ctypes.POINTER(f32), ctypes.POINTER(f32), i32,
                                        vp, i32, ctypes.POINTER(i32), _CTensor, _CTensor, vp]
     lib.kvcomm_align_kv_q8.restype = ctypes.c_int
+    lib.kvcomm_align_kv_q8_batch.argtypes = [mp, i32, _CTensor, ctypes.POINTER(_CAlignQ8Job), i32, vp]
+    lib.kvcomm_align_kv_q8_batch.restype = ctypes.c_int
     lib.kvcomm_status_string.argtypes = [ctypes.c_int]
     lib.kvcomm_status_string.restype = ctypes.c_char_p
     lib.kvcomm_version.argtypes = []
@@ -421,17 +432,13 @@ def kvcomm_align_kv_batch(model, jobs, gran=W_TOKEN, stream=None):
         if A:
             if w is None or w.dtype != torch.float32 or not w.is_contiguous():
                 raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
-            if gran == W_SEGMENT:
-                ok = w.numel() == A
-            else:
-                ok = w.numel() == kvcomm_weight_slots(model, S, gran) * A
-            if not ok:
-                raise KVCommError(-1, "weights: wrong number of elements for this granularity")
+            if w.numel() % A:
+                raise KVCommError(-1, "weights: expected [n, A]")
         keep.append((pk, pv, lens, adp))
         d = lambda t, what: _desc(t, model.dtype, what)
         cjobs[j] = _CAlignJob(d(jd["base_k"], "base_k"), d(jd["base_v"], "base_v"), d(jd["out_k"], "out_k"),
                               d(jd["out_v"], "out_v"), S, int(jd["delta_pos"]), pk, pv, lens, adp, A,
-                              None if w is None else w.data_ptr())
+                              None if w is None else w.data_ptr(), 0 if (w is None or not A) else w.numel() // A)
     _check(lib.kvcomm_align_kv_batch(ctypes.byref(model.c()), gran,
                                      layout if layout is not None else _CTensor(None, 0, 0, 0), cjobs, n,
                                      _stream_ptr(stream)))
@@ -488,3 +495,50 @@ def kvcomm_align_kv_q8(model, base_k, base_v, anchor_dk8, anchor_dv8, scale_k, s
                                   _desc(out_k, model.dtype, "out_k"), _desc(out_v, model.dtype, "out_v"),
                                   _stream_ptr(stream)))
     return out_k, out_v
+
+
+def kvcomm_align_kv_q8_batch(model, jobs, gran=W_TOKEN, stream=None):
+    """The compressed update of several segments in one launch.
+
+    jobs: list of dicts with base_k, base_v, anchor_dk8, anchor_dv8 (lists of uint8 tensors), scale_k, scale_v
+    (lists of floats), weights, delta_pos, out_k, out_v and optionally anchor_len, anchor_delta_pos."""
+    lib = load_library()
+    n = len(jobs)
+    cjobs = (_CAlignQ8Job * max(n, 1))()
+    keep, layout = [], None
+    for j, jd in enumerate(jobs):
+        dk8, dv8 = jd["anchor_dk8"], jd["anchor_dv8"]
+        A = len(dk8)
+        if len(dv8) != A or len(jd["scale_k"]) != A or len(jd["scale_v"]) != A:
+            raise KVCommError(-1, "anchor lists and scales differ in length")
+        pk = pv = lens = sk = sv = adp = None
+        if A:
+            lay = _desc_q8(dk8[0], "anchor_dk8")
+            for a in list(dk8) + list(dv8):
+                if not _same_layout(lay, _desc_q8(a, "anchor deviations")):
+                    raise KVCommError(-1, "all compressed anchors must share one layout")
+            if layout is not None and not _same_layout(layout, lay):
+                raise KVCommError(-1, "all anchors of a batched call must share one layout")
+            layout = lay
+            pk = (ctypes.c_void_p * A)(*[a.data_ptr() for a in dk8])
+            pv = (ctypes.c_void_p * A)(*[a.data_ptr() for a in dv8])
+            al = jd.get("anchor_len")
+            lens = (ctypes.c_int32 * A)(*[int(x) for x in (al if al is not None else [a.shape[2] for a in dk8])])
+            sk = (ctypes.c_float * A)(*[float(x) for x in jd["scale_k"]])
+            sv = (ctypes.c_float * A)(*[float(x) for x in jd["scale_v"]])
+        if jd.get("anchor_delta_pos") is not None:
+            if len(jd["anchor_delta_pos"]) != A:
+                raise KVCommError(-1, "anchor_delta_pos must have one entry per anchor")
+            adp = (ctypes.c_int32 * max(A, 1))(*[int(x) for x in jd["anchor_delta_pos"]])
+        w = jd.get("weights")
+        if A and (w is None or w.dtype != torch.float32 or not w.is_contiguous() or w.numel() % A):
+            raise KVCommError(-1, "weights: expected a contiguous fp32 device tensor [n, A]")
+        keep.append((pk, pv, lens, sk, sv, adp))
+        d = lambda t, what: _desc(t, model.dtype, what)
+        cjobs[j] = _CAlignQ8Job(d(jd["base_k"], "base_k"), d(jd["base_v"], "base_v"), d(jd["out_k"], "out_k"),
+                                d(jd["out_v"], "out_v"), jd["base_k"].shape[2], int(jd["delta_pos"]), pk, pv, lens, adp,
+                                sk, sv, A, None if w is None else w.data_ptr(),
+                                0 if (w is None or not A) else w.numel() // A)
+    _check(lib.kvcomm_align_kv_q8_batch(ctypes.byref(model.c()), gran,
+                                        layout if layout is not None else _CTensor(None, 0, 0, 0), cjobs, n,
+                                        _stream_ptr(stream)))

@@ -17,9 +17,7 @@
 // non-temporal.  Per-token anchor weights and the cos/sin tables load once per block (LDS).
 // cos/sin: the angle delta * theta^(-2i/D) is formed and reduced modulo 2*pi in double from a
 // host-computed frequency table (kernel argument); sine and cosine of the reduced angle are fp32.
-#include <math.h>
-
-#include "kvcomm_device.h"
+#include "align_common.h"
 
 namespace {
 
@@ -36,27 +34,8 @@ using namespace kvc;
 #define KVC_ALIGN_WPE 4   // wavefronts per SIMD the register budget is sized for (measured best: 4 with 2 anchors in flight)
 #endif
 
-constexpr int kBlock = 256;
+constexpr int kBlock = kAlignBlock;
 constexpr int kAnchorsInFlight = KVC_ALIGN_INFLIGHT;
-constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
-constexpr int kMaxHalf = 128;  // head_dim / 2 for the largest supported head_dim
-
-// One segment of a launch.  A launch covers up to KVCOMM_MAX_BATCH segments (all placeholders of an
-// agent, and the prefix segments that follow them, are independent and are updated "in parallel").
-struct AlignJob {
-    const void *base[2];   // [0] keys, [1] values
-    void *out[2];
-    Strides s_base[2], s_out[2];
-    const float *weights;
-    int32_t S;                 // tokens
-    int32_t w_pitch;           // anchors per weight row (n_anchors of the segment)
-    int32_t n_token_tiles;
-    int32_t tile0;             // first of the segment's tiles in the launch-wide tile list
-    int16_t a0, n_sel;         // its selected anchors: entries [a0, a0 + n_sel) of anc / col / tab
-    int16_t t0, n_tab;         // its rotation tables: entries [t0, t0 + n_tab) of tab_delta
-    int16_t base_tab;          // table of the base keys' rotation (index among the segment's tables) + 1, 0 = identity
-    int16_t pad_;
-};
 
 struct AlignParams {
     AlignJob job[KVCOMM_MAX_BATCH];
@@ -84,11 +63,7 @@ __global__ __launch_bounds__(kBlock, KVC_ALIGN_WPE) void align_kernel(const Alig
     // write neighbouring slices of the same cache rows when the segments of a launch are adjacent.
     const int chunk = blockIdx.x / p.tiles_total;
     const int r = blockIdx.x % p.tiles_total;
-    int ji = 0;
-#pragma unroll
-    for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
-        if (i < p.n_jobs && r >= p.job[i].tile0) ji = i;
-    const AlignJob &jb = p.job[ji];
+    const AlignJob &jb = p.job[job_of_tile(p, r)];
     const int n_sel = jb.n_sel, a0 = jb.a0;
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -215,8 +190,7 @@ int launch_align(const AlignParams &p, int n_blocks, int max_tab, int max_sel, h
     constexpr int HALF = LPR * Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
     const size_t lds = sizeof(float2) * (size_t)max_tab * HALF + sizeof(float) * (size_t)RPB * max_sel;
-    hipLaunchKernelGGL((align_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
-    return launch_status();
+    return launch(align_kernel<T, LPR>, dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
 }
 
 }  // namespace
@@ -224,126 +198,25 @@ int launch_align(const AlignParams &p, int n_blocks, int max_tab, int max_sel, h
 extern "C" int kvcomm_align_kv_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
                                      const kvcomm_align_job *jobs, int32_t n_jobs, void *stream)
 {
-    int st = check_model(model);
-    if (st) return st;
-    if ((st = check_gran(gran))) return st;
-    if (!jobs || n_jobs <= 0) return KVCOMM_EINVAL;
-    if (n_jobs > KVCOMM_MAX_BATCH) return KVCOMM_EUNSUPPORTED;
-    const int dt = model->dtype;
-    bool any_anchor = false;
-    for (int j = 0; j < n_jobs; ++j) {
-        const kvcomm_align_job &jd = jobs[j];
-        if (jd.seg_len <= 0 || jd.n_anchors < 0) return KVCOMM_EINVAL;
-        if (jd.n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
-        if ((st = check_tensor(jd.base_k, dt, true)) || (st = check_tensor(jd.base_v, dt, true)) ||
-            (st = check_tensor(jd.out_k, dt, true)) || (st = check_tensor(jd.out_v, dt, true)))
-            return st;
-        if (jd.n_anchors > 0) {
-            if (!jd.anchor_dk || !jd.anchor_dv || !jd.anchor_len || !jd.weights) return KVCOMM_EINVAL;
-            any_anchor = true;
-        }
-    }
-    if (any_anchor && (st = check_tensor(anchor_layout, dt, false))) return st;
-
     AlignParams p{};
-    p.s_anc = strides_of(anchor_layout);
-    p.H = model->n_kv_heads;
-    p.LH = model->n_layers * model->n_kv_heads;
-    p.gran = gran;
-    p.n_jobs = n_jobs;
-    for (int i = 0; i < model->head_dim / 2; ++i)
-        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
-
-    const int es = elem_size(dt);
-    const int lpr = model->head_dim / (2 * (16 / es));
-    const int rpb = kBlock / lpr;
-    int n_tab_total = 0, n_sel_total = 0, max_tab = 0, max_sel = 0;
-    int64_t tiles_total = 0;
-    for (int j = 0; j < n_jobs; ++j) {
-        const kvcomm_align_job &jd = jobs[j];
-        AlignJob &jb = p.job[j];
-        jb.base[0] = jd.base_k.ptr;
-        jb.base[1] = jd.base_v.ptr;
-        jb.out[0] = jd.out_k.ptr;
-        jb.out[1] = jd.out_v.ptr;
-        jb.s_base[0] = strides_of(jd.base_k);
-        jb.s_base[1] = strides_of(jd.base_v);
-        jb.s_out[0] = strides_of(jd.out_k);
-        jb.s_out[1] = strides_of(jd.out_v);
-        jb.weights = jd.weights;
-        jb.S = jd.seg_len;
-        jb.w_pitch = jd.n_anchors;
-        jb.a0 = (int16_t)n_sel_total;
-        jb.t0 = (int16_t)n_tab_total;
-        // Rotation tables of the segment: one per distinct non-zero position delta (base keys: delta_pos;
-        // anchor a's deviation: delta_pos - anchor_delta_pos[a]).
-        int n_tab = 0;
-        bool overflow = false;
-        auto table_of = [&](int32_t d) -> int {
-            if (d == 0) return 0;
-            for (int r = 0; r < n_tab; ++r)
-                if (p.tab_delta[n_tab_total + r] == d) return r + 1;
-            if (n_tab_total + n_tab >= kMaxTab) {
-                overflow = true;
-                return 0;
-            }
-            p.tab_delta[n_tab_total + n_tab] = d;
-            return ++n_tab;
-        };
-        jb.base_tab = (int16_t)table_of(jd.delta_pos);
-        int n_sel = 0;
-        for (int a = 0; a < jd.n_anchors; ++a) {
-            if (jd.anchor_len[a] < 0) return KVCOMM_EINVAL;
-            if (jd.anchor_len[a] < jd.seg_len) continue;  // not selected: never read
-            if (!jd.anchor_dk[a] || !jd.anchor_dv[a] || !aligned16(jd.anchor_dk[a]) || !aligned16(jd.anchor_dv[a]))
-                return KVCOMM_EINVAL;
-            if (n_sel_total + n_sel >= KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;  // over all segments of the launch
-            const int s = n_sel_total + n_sel++;
-            p.anc[0][s] = jd.anchor_dk[a];
-            p.anc[1][s] = jd.anchor_dv[a];
-            p.col[s] = (uint8_t)a;
-            p.tab[s] = (uint8_t)(jd.anchor_delta_pos ? table_of(jd.delta_pos - jd.anchor_delta_pos[a]) : 0);
-        }
-        if (overflow) return KVCOMM_EUNSUPPORTED;
-        jb.n_sel = (int16_t)n_sel;
-        jb.n_tab = (int16_t)n_tab;
-        n_sel_total += n_sel;
-        n_tab_total += n_tab;
-        max_tab = n_tab > max_tab ? n_tab : max_tab;
-        max_sel = n_sel > max_sel ? n_sel : max_sel;
-        jb.n_token_tiles = (jd.seg_len + rpb - 1) / rpb;
-        tiles_total += jb.n_token_tiles;
-    }
-
-    // Many small blocks: the memory system delivers more with more wavefronts in flight, and the
-    // per-block set-up (weights, cos/sin) is a few dozen instructions.
-    const int64_t target_blocks = (int64_t)KVC_ALIGN_BLOCKS * n_jobs;
-    int64_t n_chunks = (target_blocks + tiles_total - 1) / tiles_total;
-    if (n_chunks > p.LH) n_chunks = p.LH;
-    if (n_chunks < 1) n_chunks = 1;
-    p.lh_per_block = (int32_t)((p.LH + n_chunks - 1) / n_chunks);
-    n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
-    int32_t tile0 = 0;
-    for (int j = 0; j < n_jobs; ++j) {
-        p.job[j].tile0 = tile0;
-        tile0 += p.job[j].n_token_tiles;
-    }
-    p.tiles_total = (int32_t)tiles_total;
-    const int64_t n_blocks = n_chunks * tiles_total;
-    if (n_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
+    AlignLaunch pl{};
+    const int es = model ? elem_size(model->dtype) : 2;
+    int st = plan_align(model, gran, anchor_layout, es, jobs, n_jobs, KVC_ALIGN_BLOCKS, p, pl,
+                        [](int, const kvcomm_align_job &, int) { return (int)KVCOMM_OK; });
+    if (st) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-
-    if (dt == KVCOMM_BF16) {
-        switch (lpr) {
-            case 4: return launch_align<bf16_t, 4>(p, (int)n_blocks, max_tab, max_sel, s);
-            case 8: return launch_align<bf16_t, 8>(p, (int)n_blocks, max_tab, max_sel, s);
-            case 16: return launch_align<bf16_t, 16>(p, (int)n_blocks, max_tab, max_sel, s);
+    const int nb = (int)pl.n_blocks;
+    if (model->dtype == KVCOMM_BF16) {
+        switch (pl.lpr) {
+            case 4: return launch_align<bf16_t, 4>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 8: return launch_align<bf16_t, 8>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 16: return launch_align<bf16_t, 16>(p, nb, pl.max_tab, pl.max_sel, s);
         }
     } else {
-        switch (lpr) {
-            case 8: return launch_align<float, 8>(p, (int)n_blocks, max_tab, max_sel, s);
-            case 16: return launch_align<float, 16>(p, (int)n_blocks, max_tab, max_sel, s);
-            case 32: return launch_align<float, 32>(p, (int)n_blocks, max_tab, max_sel, s);
+        switch (pl.lpr) {
+            case 8: return launch_align<float, 8>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 16: return launch_align<float, 16>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 32: return launch_align<float, 32>(p, nb, pl.max_tab, pl.max_sel, s);
         }
     }
     return KVCOMM_EUNSUPPORTED;
@@ -368,5 +241,6 @@ extern "C" int kvcomm_align_kv(const kvcomm_model *model, int32_t gran, kvcomm_t
     job.anchor_delta_pos = anchor_delta_pos;
     job.n_anchors = n_anchors;
     job.weights = weights;
+    job.weights_slots = check_model(model) || check_gran(gran) ? 0 : (int64_t)kvcomm_weight_slots(model, seg_len, gran);
     return kvcomm_align_kv_batch(model, gran, anchor_layout, &job, 1, stream);
 }

@@ -162,8 +162,7 @@ __global__ __launch_bounds__(kBlock) void capture_kernel(const CaptureParams p)
 template <typename T, int LPR>
 int launch_capture(const CaptureParams &p, int n_blocks, hipStream_t stream)
 {
-    hipLaunchKernelGGL((capture_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), 0, stream, p);
-    return launch_status();
+    return launch(capture_kernel<T, LPR>, dim3(n_blocks, 2), dim3(kBlock), 0, stream, p);
 }
 
 }  // namespace
@@ -205,10 +204,8 @@ extern "C" int kvcomm_anchor_predict(const float *weights, int64_t n_slots, cons
     p.longer = seg_len > max_len;
     p.gamma = (double)gamma;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(entropy_partial_kernel, dim3(p.n_blocks), dim3(kBlock), 0, s, p);
-    if (hipGetLastError() != hipSuccess) return KVCOMM_EHIP;
-    hipLaunchKernelGGL(predict_final_kernel, dim3(1), dim3(kBlock), 0, s, p);
-    return launch_status();
+    if (int st = launch(entropy_partial_kernel, dim3(p.n_blocks), dim3(kBlock), 0, s, p)) return st;
+    return launch(predict_final_kernel, dim3(1), dim3(kBlock), 0, s, p);
 }
 
 extern "C" int kvcomm_capture_offsets(const kvcomm_model *model, kvcomm_tensor base_k, kvcomm_tensor base_v,

@@ -496,18 +496,13 @@ __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalPar
 template <typename T, int LPR>
 int launch_dist(const DistParams &p, int n_blocks, int max_sel, bool cosine, hipStream_t stream)
 {
-    if (p.fused) {
-        hipLaunchKernelGGL((dist_row_softmax_kernel<T, LPR>), dim3(n_blocks), dim3(kBlock), 0, stream, p);
-        return launch_status();
-    }
+    if (p.fused) return launch(dist_row_softmax_kernel<T, LPR>, dim3(n_blocks), dim3(kBlock), 0, stream, p);
     if (cosine) {
         const int a_tiles = (max_sel + kCosTile - 1) / kCosTile;
-        hipLaunchKernelGGL((cos_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
-    } else {
-        const int a_tiles = (max_sel + kAnchorTile - 1) / kAnchorTile;
-        hipLaunchKernelGGL((dist_partial_kernel<T, LPR>), dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
+        return launch(cos_partial_kernel<T, LPR>, dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
     }
-    return launch_status();
+    const int a_tiles = (max_sel + kAnchorTile - 1) / kAnchorTile;
+    return launch(dist_partial_kernel<T, LPR>, dim3(n_blocks, a_tiles), dim3(kBlock), 0, stream, p);
 }
 
 int check_rule(int rule)
@@ -699,10 +694,8 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
     }
     if (fused) return KVCOMM_OK;
     if (gran == KVCOMM_W_SEGMENT)
-        hipLaunchKernelGGL(finalize_segment_kernel, dim3(n_jobs), dim3(kBlock), 0, s, fp);
-    else
-        hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)final_blocks), dim3(kBlock), 0, s, fp);
-    return launch_status();
+        return launch(finalize_segment_kernel, dim3(n_jobs), dim3(kBlock), 0, s, fp);
+    return launch(finalize_kernel, dim3((unsigned)final_blocks), dim3(kBlock), 0, s, fp);
 }
 
 extern "C" int kvcomm_anchor_weights_rule(const kvcomm_model *model, int32_t gran, int32_t rule, float temperature,

@@ -9,21 +9,17 @@
 //                            weight, so the inner loop is that of the uncompressed kernel plus the unpacking.
 // gfx950's v_cvt_pk_f32_fp8 / v_cvt_pk_fp8_f32 implement exactly this format; the encoder clamps first, so
 // the hardware's own overflow behaviour never matters.
-#include <math.h>
-
-#include "kvcomm_device.h"
+#include "align_common.h"
 
 namespace {
 
 using namespace kvc;
 
 #ifndef KVC_ALIGNQ8_BLOCKS
-#define KVC_ALIGNQ8_BLOCKS 2048   // blocks per tensor the grid of the compressed update aims at
+#define KVC_ALIGNQ8_BLOCKS 2048   // blocks per tensor and segment the grid of the compressed update aims at
 #endif
 
-constexpr int kBlock = 256;
-constexpr int kMaxTab = KVCOMM_MAX_ANCHORS + 1;
-constexpr int kMaxHalf = 128;
+constexpr int kBlock = kAlignBlock;
 
 // EPV consecutive E4M3 bytes -> floats.
 template <int EPV>
@@ -105,13 +101,20 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const QuantParams p)
     uint32_t w[EPV / 4];
 #pragma unroll
     for (int i = 0; i < EPV / 4; ++i) {
+        // The clamp (maximum / minimum by number) turns a NaN into a bound, so NaN inputs are patched
+        // afterwards: their code is 0x7f, the format's NaN, whatever the sign.
         float c[4];
+        uint32_t nan_bytes = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = fminf(fmaxf(x[4 * i + e] * p.inv_scale, -448.f), 448.f);  // NaN stays NaN
+        for (int e = 0; e < 4; ++e) {
+            const float v = x[4 * i + e] * p.inv_scale;
+            c[e] = fminf(fmaxf(v, -448.f), 448.f);
+            nan_bytes |= v != v ? 0xffu << (8 * e) : 0u;
+        }
         int packed = 0;
         packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], packed, false);
         packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], packed, true);
-        w[i] = (uint32_t)packed;
+        w[i] = ((uint32_t)packed & ~nan_bytes) | (0x7f7f7f7fu & nan_bytes);
     }
     uint8_t *yp = p.out + l * p.s_out.layer + h * p.s_out.head + t * p.s_out.token + lir * EPV;
     if constexpr (EPV == 8) {
@@ -123,26 +126,28 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(const QuantParams p)
 }
 
 // --------------------------------------------------------------------------------- align
+// Same launch-wide layout as the uncompressed update (per-segment descriptors, selected anchors and rotation
+// tables of all segments in the kernel arguments); a deviation's power-of-two scale travels as its exponent.
 struct AlignQ8Params {
-    const void *base[2];   // [0] keys, [1] values
-    void *out[2];
-    Strides s_base[2], s_out[2], s_anc;   // s_anc in bytes (= elements of the E4M3 tensors)
-    const float *weights;
-    int32_t H, S, LH;
-    int32_t w_pitch, n_sel, gran;
-    int32_t lh_per_block, n_token_tiles;
-    int32_t n_tab, base_tab;
+    AlignJob job[KVCOMM_MAX_BATCH];
+    Strides s_anc;             // in bytes (= elements of the E4M3 tensors)
+    int32_t H, LH;
+    int32_t gran, n_jobs;
+    int32_t lh_per_block;
+    int32_t tiles_total;
     int32_t tab_delta[kMaxTab];
-    const uint8_t *anc[2][KVCOMM_MAX_ANCHORS];
-    float scale[2][KVCOMM_MAX_ANCHORS];   // [0] key, [1] value deviation scale of a selected anchor
+    const void *anc[2][KVCOMM_MAX_ANCHORS];
+    int8_t scale_exp[2][KVCOMM_MAX_ANCHORS];   // [0] key, [1] value deviation scale = 2^scale_exp of a selected anchor
     uint8_t col[KVCOMM_MAX_ANCHORS];
     uint8_t tab[KVCOMM_MAX_ANCHORS];
     double inv_freq[kMaxHalf];
 };
 static_assert(sizeof(AlignQ8Params) <= 4096, "kernel arguments are limited to 4 KB");
 
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }  // -126 <= e <= 127
+
 // Work split as in align_kernel: LPR = D / (2 * EPV) lanes per row, lane r owns channels [r*EPV, r*EPV+EPV)
-// of both halves; a block is 256 / LPR tokens of a run of (layer, head) pairs of ONE tensor.
+// of both halves; a block is 256 / LPR tokens of a run of (layer, head) pairs of ONE tensor of one segment.
 template <typename T, int LPR>
 __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params p)
 {
@@ -150,56 +155,61 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
     constexpr int HALF = LPR * EPV;
     constexpr int RPB = kBlock / LPR;
 
+    const int chunk = blockIdx.x / p.tiles_total;
+    const int r = blockIdx.x % p.tiles_total;
+    const AlignJob &jb = p.job[job_of_tile(p, r)];
+    const int n_sel = jb.n_sel, a0 = jb.a0;
+
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    float2 *cs = reinterpret_cast<float2 *>(smem_raw);                        // [n_tab][HALF]
-    float *w_lds = reinterpret_cast<float *>(smem_raw) + 2 * p.n_tab * HALF;  // [RPB][n_sel], scale folded in
+    float2 *cs = reinterpret_cast<float2 *>(smem_raw);                         // [n_tab][HALF]
+    float *w_lds = reinterpret_cast<float *>(smem_raw) + 2 * jb.n_tab * HALF;  // [RPB][n_sel], scale folded in
 
     const int tid = threadIdx.x;
     const int row = tid / LPR, lir = tid % LPR;
-    const int tile = blockIdx.x % p.n_token_tiles;
-    const int chunk = blockIdx.x / p.n_token_tiles;
+    const int tile = r - jb.tile0;
     const int which = blockIdx.y;
     const bool is_k = which == 0;
     const int t = tile * RPB + row;
-    const bool valid = t < p.S;
+    const bool valid = t < jb.S;
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
     if (is_k)
-        for (int idx = tid; idx < p.n_tab * HALF; idx += kBlock)
-            cs[idx] = rope_cos_sin(p.tab_delta[idx / HALF], p.inv_freq[idx % HALF]);
+        for (int idx = tid; idx < jb.n_tab * HALF; idx += kBlock)
+            cs[idx] = rope_cos_sin(p.tab_delta[jb.t0 + idx / HALF], p.inv_freq[idx % HALF]);
     if (p.gran != KVCOMM_W_LAYER_HEAD_TOKEN) {
-        for (int idx = tid; idx < RPB * p.n_sel; idx += kBlock) {
-            const int r = idx / p.n_sel, a = idx % p.n_sel;
-            const int tt = tile * RPB + r;
+        for (int idx = tid; idx < RPB * n_sel; idx += kBlock) {
+            const int rr = idx / n_sel, a = idx % n_sel;
+            const int tt = tile * RPB + rr;
             const int64_t slot = p.gran == KVCOMM_W_TOKEN ? tt : 0;
-            w_lds[idx] = tt < p.S ? p.weights[slot * p.w_pitch + p.col[a]] * p.scale[which][a] : 0.f;
+            w_lds[idx] = tt < jb.S ? jb.weights[slot * jb.w_pitch + p.col[a0 + a]] * pow2f(p.scale_exp[which][a0 + a]) : 0.f;
         }
     }
     __syncthreads();
     if (!valid) return;
 
-    const bool rot_base = is_k && p.base_tab != 0;
+    const bool rot_base = is_k && jb.base_tab != 0;
     float bc[EPV], bs[EPV];
     if (rot_base) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            const float2 v = cs[(p.base_tab - 1) * HALF + lir * EPV + e];
+            const float2 v = cs[(jb.base_tab - 1) * HALF + lir * EPV + e];
             bc[e] = v.x;
             bs[e] = v.y;
         }
     }
-    const T *bp = static_cast<const T *>(p.base[which]);
-    T *op = static_cast<T *>(p.out[which]);
-    const Strides sb = p.s_base[which], so = p.s_out[which];
+    const T *bp = static_cast<const T *>(jb.base[which]);
+    T *op = static_cast<T *>(jb.out[which]);
+    const Strides sb = jb.s_base[which], so = jb.s_out[which];
     const int64_t col0 = (int64_t)lir * EPV;
+    auto anchor_row = [&](int a) { return static_cast<const uint8_t *>(p.anc[which][a0 + a]); };
 
     for (int lh = lh0; lh < lh1; ++lh) {
         const int l = lh / p.H, h = lh % p.H;
         const T *xp = bp + l * sb.layer + h * sb.head + t * sb.token + col0;
         const u32x4 rlo = load16_stream(xp), rhi = load16_stream(xp + HALF);
         const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + col0;
-        const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN ? p.weights + ((int64_t)lh * p.S + t) * p.w_pitch : nullptr;
+        const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN ? jb.weights + ((int64_t)lh * jb.S + t) * jb.w_pitch : nullptr;
 
         float lo[EPV], hi[EPV];
         unpack<T>(rlo, lo);
@@ -213,11 +223,11 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
             }
         }
         auto accumulate = [&](int a, const uint32_t (&rdlo)[EPV / 4], const uint32_t (&rdhi)[EPV / 4]) {
-            const float w = wrow ? wrow[p.col[a]] * p.scale[which][a] : w_lds[row * p.n_sel + a];
+            const float w = wrow ? wrow[p.col[a0 + a]] * pow2f(p.scale_exp[which][a0 + a]) : w_lds[row * n_sel + a];
             float dlo[EPV], dhi[EPV];
             unpack_q8<EPV>(rdlo, dlo);
             unpack_q8<EPV>(rdhi, dhi);
-            const int tb = is_k ? p.tab[a] : 0;
+            const int tb = is_k ? p.tab[a0 + a] : 0;
             if (tb) {
                 const float2 *tcs = cs + (tb - 1) * HALF + lir * EPV;
 #pragma unroll
@@ -241,10 +251,10 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
             const bool odd = lir & 1;
             const int64_t roff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token;
             const int pair_off = 8 * (lir & ~1);
-            for (; a + 4 <= p.n_sel; a += 4) {
+            for (; a + 4 <= n_sel; a += 4) {
                 Q8Pair x[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) x[u] = load_q8_pair(p.anc[which][a + u] + roff, pair_off, odd, HALF);
+                for (int u = 0; u < 4; ++u) x[u] = load_q8_pair(anchor_row(a + u) + roff, pair_off, odd, HALF);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     uint32_t x0[2], x1[2];
@@ -252,26 +262,26 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
                     accumulate(a + u, x0, x1);
                 }
             }
-            for (; a < p.n_sel; ++a) {
+            for (; a < n_sel; ++a) {
                 uint32_t x0[2], x1[2];
-                split_q8_pair(load_q8_pair(p.anc[which][a] + roff, pair_off, odd, HALF), odd, x0, x1);
+                split_q8_pair(load_q8_pair(anchor_row(a) + roff, pair_off, odd, HALF), odd, x0, x1);
                 accumulate(a, x0, x1);
             }
         } else {
-            for (; a + 4 <= p.n_sel; a += 4) {
+            for (; a + 4 <= n_sel; a += 4) {
                 uint32_t x[4][2][EPV / 4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const uint8_t *d = p.anc[which][a + u] + aoff;
+                    const uint8_t *d = anchor_row(a + u) + aoff;
                     load_q8<EPV>(d, x[u][0]);
                     load_q8<EPV>(d + HALF, x[u][1]);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
             }
-            for (; a < p.n_sel; ++a) {
+            for (; a < n_sel; ++a) {
                 uint32_t x0[EPV / 4], x1[EPV / 4];
-                const uint8_t *d = p.anc[which][a] + aoff;
+                const uint8_t *d = anchor_row(a) + aoff;
                 load_q8<EPV>(d, x0);
                 load_q8<EPV>(d + HALF, x1);
                 accumulate(a, x0, x1);
@@ -284,13 +294,12 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
 }
 
 template <typename T, int LPR>
-int launch_align_q8(const AlignQ8Params &p, int n_blocks, hipStream_t stream)
+int launch_align_q8(const AlignQ8Params &p, int n_blocks, int max_tab, int max_sel, hipStream_t stream)
 {
     constexpr int HALF = LPR * Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
-    const size_t lds = sizeof(float2) * (size_t)p.n_tab * HALF + sizeof(float) * (size_t)RPB * p.n_sel;
-    hipLaunchKernelGGL((align_q8_kernel<T, LPR>), dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
-    return launch_status();
+    const size_t lds = sizeof(float2) * (size_t)max_tab * HALF + sizeof(float) * (size_t)RPB * max_sel;
+    return launch(align_q8_kernel<T, LPR>, dim3(n_blocks, 2), dim3(kBlock), lds, stream, p);
 }
 
 // Byte tensors: pointer 16-byte aligned, strides multiples of 16 bytes.
@@ -302,11 +311,14 @@ int check_tensor_q8(const kvcomm_tensor &t, bool need_ptr)
     return KVCOMM_OK;
 }
 
-bool power_of_two(float s)
+// s = 2^e with -126 <= e <= 127 (a normal power of two)?  Writes e.
+bool power_of_two(float s, int *exp_out = nullptr)
 {
     if (!(s > 0.f) || !isfinite(s)) return false;
     int e;
-    return frexpf(s, &e) == 0.5f;
+    if (frexpf(s, &e) != 0.5f || e - 1 < -126) return false;
+    if (exp_out) *exp_out = e - 1;
+    return true;
 }
 
 }  // namespace
@@ -337,18 +349,53 @@ extern "C" int kvcomm_quantize_deltas(const kvcomm_model *model, kvcomm_tensor i
     st = KVCOMM_EUNSUPPORTED;
     if (dt == KVCOMM_BF16) {
         switch (lpr) {
-            case 8: hipLaunchKernelGGL((quantize_kernel<bf16_t, 8>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
-            case 16: hipLaunchKernelGGL((quantize_kernel<bf16_t, 16>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
-            case 32: hipLaunchKernelGGL((quantize_kernel<bf16_t, 32>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 8: return launch(quantize_kernel<bf16_t, 8>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+            case 16: return launch(quantize_kernel<bf16_t, 16>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+            case 32: return launch(quantize_kernel<bf16_t, 32>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
         }
     } else {
         switch (lpr) {
-            case 16: hipLaunchKernelGGL((quantize_kernel<float, 16>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
-            case 32: hipLaunchKernelGGL((quantize_kernel<float, 32>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
-            case 64: hipLaunchKernelGGL((quantize_kernel<float, 64>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p); st = 0; break;
+            case 16: return launch(quantize_kernel<float, 16>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+            case 32: return launch(quantize_kernel<float, 32>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+            case 64: return launch(quantize_kernel<float, 64>, dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
         }
     }
-    return st ? st : launch_status();
+    return st;
+}
+
+extern "C" int kvcomm_align_kv_q8_batch(const kvcomm_model *model, int32_t gran, kvcomm_tensor anchor_layout,
+                                        const kvcomm_align_q8_job *jobs, int32_t n_jobs, void *stream)
+{
+    AlignQ8Params p{};
+    AlignLaunch pl{};
+    for (int j = 0; jobs && j < n_jobs && j < KVCOMM_MAX_BATCH; ++j)
+        if (jobs[j].n_anchors > 0 && (!jobs[j].anchor_scale_k || !jobs[j].anchor_scale_v)) return KVCOMM_EINVAL;
+    int st = plan_align(model, gran, anchor_layout, 1, jobs, n_jobs, KVC_ALIGNQ8_BLOCKS, p, pl,
+                        [&p](int slot, const kvcomm_align_q8_job &jd, int a) {
+                            int ek, ev;
+                            if (!power_of_two(jd.anchor_scale_k[a], &ek) || !power_of_two(jd.anchor_scale_v[a], &ev))
+                                return (int)KVCOMM_EINVAL;
+                            p.scale_exp[0][slot] = (int8_t)ek;
+                            p.scale_exp[1][slot] = (int8_t)ev;
+                            return (int)KVCOMM_OK;
+                        });
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int nb = (int)pl.n_blocks;
+    if (model->dtype == KVCOMM_BF16) {
+        switch (pl.lpr) {
+            case 4: return launch_align_q8<bf16_t, 4>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 8: return launch_align_q8<bf16_t, 8>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 16: return launch_align_q8<bf16_t, 16>(p, nb, pl.max_tab, pl.max_sel, s);
+        }
+    } else {
+        switch (pl.lpr) {
+            case 8: return launch_align_q8<float, 8>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 16: return launch_align_q8<float, 16>(p, nb, pl.max_tab, pl.max_sel, s);
+            case 32: return launch_align_q8<float, 32>(p, nb, pl.max_tab, pl.max_sel, s);
+        }
+    }
+    return KVCOMM_EUNSUPPORTED;
 }
 
 extern "C" int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran, kvcomm_tensor base_k, kvcomm_tensor base_v,
@@ -358,81 +405,21 @@ extern "C" int kvcomm_align_kv_q8(const kvcomm_model *model, int32_t gran, kvcom
                                   int32_t delta_pos, const int32_t *anchor_delta_pos, kvcomm_tensor out_k,
                                   kvcomm_tensor out_v, void *stream)
 {
-    int st = check_model(model);
-    if (st) return st;
-    if ((st = check_gran(gran))) return st;
-    if (seg_len <= 0 || n_anchors < 0) return KVCOMM_EINVAL;
-    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
-    const int dt = model->dtype;
-    if ((st = check_tensor(base_k, dt, true)) || (st = check_tensor(base_v, dt, true)) ||
-        (st = check_tensor(out_k, dt, true)) || (st = check_tensor(out_v, dt, true)))
-        return st;
-    if (n_anchors > 0) {
-        if (!anchor_dk || !anchor_dv || !anchor_len || !anchor_scale_k || !anchor_scale_v || !weights) return KVCOMM_EINVAL;
-        if ((st = check_tensor_q8(anchor_layout, false))) return st;
-    }
-    AlignQ8Params p{};
-    p.base[0] = base_k.ptr;
-    p.base[1] = base_v.ptr;
-    p.out[0] = out_k.ptr;
-    p.out[1] = out_v.ptr;
-    p.s_base[0] = strides_of(base_k);
-    p.s_base[1] = strides_of(base_v);
-    p.s_out[0] = strides_of(out_k);
-    p.s_out[1] = strides_of(out_v);
-    p.s_anc = strides_of(anchor_layout);
-    p.weights = weights;
-    p.H = model->n_kv_heads;
-    p.S = seg_len;
-    p.LH = model->n_layers * model->n_kv_heads;
-    p.w_pitch = n_anchors;
-    p.gran = gran;
-    for (int i = 0; i < model->head_dim / 2; ++i)
-        p.inv_freq[i] = pow(model->rope_theta, -2.0 * (double)i / (double)model->head_dim);
-    auto table_of = [&](int32_t d) -> int {
-        if (d == 0) return 0;
-        for (int r = 0; r < p.n_tab; ++r)
-            if (p.tab_delta[r] == d) return r + 1;
-        p.tab_delta[p.n_tab] = d;
-        return ++p.n_tab;
-    };
-    p.base_tab = table_of(delta_pos);
-    for (int a = 0; a < n_anchors; ++a) {
-        if (anchor_len[a] < 0) return KVCOMM_EINVAL;
-        if (anchor_len[a] < seg_len) continue;
-        if (!anchor_dk[a] || !anchor_dv[a] || !aligned16(anchor_dk[a]) || !aligned16(anchor_dv[a])) return KVCOMM_EINVAL;
-        if (!power_of_two(anchor_scale_k[a]) || !power_of_two(anchor_scale_v[a])) return KVCOMM_EINVAL;
-        const int s = p.n_sel++;
-        p.anc[0][s] = static_cast<const uint8_t *>(anchor_dk[a]);
-        p.anc[1][s] = static_cast<const uint8_t *>(anchor_dv[a]);
-        p.scale[0][s] = anchor_scale_k[a];
-        p.scale[1][s] = anchor_scale_v[a];
-        p.col[s] = (uint8_t)a;
-        p.tab[s] = (uint8_t)(anchor_delta_pos ? table_of(delta_pos - anchor_delta_pos[a]) : 0);
-    }
-    const int es = elem_size(dt);
-    const int lpr = model->head_dim / (2 * (16 / es));
-    const int rpb = kBlock / lpr;
-    p.n_token_tiles = (seg_len + rpb - 1) / rpb;
-    int n_chunks = (KVC_ALIGNQ8_BLOCKS + p.n_token_tiles - 1) / p.n_token_tiles;
-    if (n_chunks > p.LH) n_chunks = p.LH;
-    if (n_chunks < 1) n_chunks = 1;
-    p.lh_per_block = (p.LH + n_chunks - 1) / n_chunks;
-    n_chunks = (p.LH + p.lh_per_block - 1) / p.lh_per_block;
-    const int n_blocks = n_chunks * p.n_token_tiles;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dt == KVCOMM_BF16) {
-        switch (lpr) {
-            case 4: return launch_align_q8<bf16_t, 4>(p, n_blocks, s);
-            case 8: return launch_align_q8<bf16_t, 8>(p, n_blocks, s);
-            case 16: return launch_align_q8<bf16_t, 16>(p, n_blocks, s);
-        }
-    } else {
-        switch (lpr) {
-            case 8: return launch_align_q8<float, 8>(p, n_blocks, s);
-            case 16: return launch_align_q8<float, 16>(p, n_blocks, s);
-            case 32: return launch_align_q8<float, 32>(p, n_blocks, s);
-        }
-    }
-    return KVCOMM_EUNSUPPORTED;
+    kvcomm_align_q8_job job{};
+    job.base_k = base_k;
+    job.base_v = base_v;
+    job.out_k = out_k;
+    job.out_v = out_v;
+    job.seg_len = seg_len;
+    job.delta_pos = delta_pos;
+    job.anchor_dk = anchor_dk;
+    job.anchor_dv = anchor_dv;
+    job.anchor_len = anchor_len;
+    job.anchor_delta_pos = anchor_delta_pos;
+    job.anchor_scale_k = anchor_scale_k;
+    job.anchor_scale_v = anchor_scale_v;
+    job.n_anchors = n_anchors;
+    job.weights = weights;
+    job.weights_slots = check_model(model) || check_gran(gran) ? 0 : (int64_t)kvcomm_weight_slots(model, seg_len, gran);
+    return kvcomm_align_kv_q8_batch(model, gran, anchor_layout, &job, 1, stream);
 }

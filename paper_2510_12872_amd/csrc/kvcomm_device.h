@@ -6,6 +6,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <utility>
+#include <vector>
+
 #include "kvcomm.h"
 
 namespace kvc {
@@ -141,9 +145,95 @@ static inline int check_gran(int gran)
                                                                                                        : KVCOMM_EINVAL;
 }
 
-static inline int launch_status()
+// ----------------------------------------------------------------- host-side aliasing checks
+// A [L, H, n, D] tensor as the caller described it: the bytes it touches are L * H runs ("blocks"), one per
+// (layer, head), each reaching from the block's first element to the last element of its last token.
+struct Extent {
+    uintptr_t base;
+    int64_t sl, sh;      // layer / head strides in bytes
+    int64_t run;         // bytes from a block's first to one past its last element
+    int32_t L, H;
+    uintptr_t lo() const { return base; }
+    uintptr_t hi() const { return base + (uintptr_t)((L - 1) * sl + (H - 1) * sh + run); }
+};
+
+static inline Extent extent_of(const kvcomm_tensor &t, int L, int H, int64_t n_tokens, int D, int es)
 {
-    return hipGetLastError() == hipSuccess ? KVCOMM_OK : KVCOMM_EHIP;
+    return Extent{reinterpret_cast<uintptr_t>(t.ptr), t.stride_layer * es, t.stride_head * es,
+                  ((n_tokens - 1) * t.stride_token + D) * es, L, H};
+}
+
+static inline Extent extent_of(const void *ptr, const kvcomm_tensor &layout, int L, int H, int64_t n_tokens, int D, int es)
+{
+    kvcomm_tensor t = layout;
+    t.ptr = const_cast<void *>(ptr);
+    return extent_of(t, L, H, n_tokens, D, es);
+}
+
+static inline Extent extent_flat(const void *ptr, size_t bytes)
+{
+    return Extent{reinterpret_cast<uintptr_t>(ptr), 0, 0, (int64_t)bytes, 1, 1};
+}
+
+// Same description (pointer, strides, shape): the in-place case.
+static inline bool same_extent(const Extent &a, const Extent &b)
+{
+    return a.base == b.base && a.sl == b.sl && a.sh == b.sh && a.run == b.run && a.L == b.L && a.H == b.H;
+}
+
+// Do two tensors touch a common byte?  Exact at the granularity of blocks (gaps between the tokens of one
+// block count as touched).  Cheap when the whole ranges are disjoint, which is the usual case.
+static inline bool extents_overlap(const Extent &a, const Extent &b)
+{
+    if (a.hi() <= b.lo() || b.hi() <= a.lo()) return false;
+    if (a.sl == b.sl && a.sh == b.sh) {
+        // Views of one allocation: block (l, h) of a meets block (l', h') of b iff the distance of their
+        // first bytes lies in (-run_b, run_a); only the index differences matter.
+        const int64_t d0 = (int64_t)(b.base - a.base);
+        const int Lm = std::max(a.L, b.L), Hm = std::max(a.H, b.H);
+        for (int dl = -(Lm - 1); dl <= Lm - 1; ++dl)
+            for (int dh = -(Hm - 1); dh <= Hm - 1; ++dh) {
+                // b's block (l + dl, h + dh) against a's block (l, h), for some l, h that keep both in range
+                if (a.L - std::max(0, -dl) - std::max(0, dl + a.L - b.L) <= 0) continue;
+                if (a.H - std::max(0, -dh) - std::max(0, dh + a.H - b.H) <= 0) continue;
+                const int64_t d = d0 + dl * a.sl + dh * a.sh;
+                if (d > -b.run && d < a.run) return true;
+            }
+        return false;
+    }
+    std::vector<std::pair<uintptr_t, uintptr_t>> blocks;
+    blocks.reserve((size_t)a.L * a.H);
+    for (int l = 0; l < a.L; ++l)
+        for (int h = 0; h < a.H; ++h) {
+            const uintptr_t lo = a.base + (uintptr_t)(l * a.sl + h * a.sh);
+            blocks.emplace_back(lo, lo + (uintptr_t)a.run);
+        }
+    std::sort(blocks.begin(), blocks.end());
+    uintptr_t reach = 0;   // running maximum of the ends, so that nested blocks are handled too
+    std::vector<uintptr_t> max_end(blocks.size());
+    for (size_t i = 0; i < blocks.size(); ++i) {
+        reach = std::max(reach, blocks[i].second);
+        max_end[i] = reach;
+    }
+    for (int l = 0; l < b.L; ++l)
+        for (int h = 0; h < b.H; ++h) {
+            const uintptr_t lo = b.base + (uintptr_t)(l * b.sl + h * b.sh), hi = lo + (uintptr_t)b.run;
+            // blocks of a that start before hi: does any of them end after lo?
+            const size_t n = std::lower_bound(blocks.begin(), blocks.end(), std::make_pair(hi, (uintptr_t)0)) - blocks.begin();
+            if (n > 0 && max_end[n - 1] > lo) return true;
+        }
+    return false;
+}
+
+// Launches a kernel that takes its parameter block by value and maps THIS launch's own return code: an
+// error that an earlier, unrelated HIP call left on the thread is neither reported nor cleared.
+template <typename P>
+static inline int launch(void (*kernel)(P), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const P &params)
+{
+    void *args[] = {const_cast<void *>(static_cast<const void *>(&params))};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, args, lds_bytes, stream) == hipSuccess
+               ? KVCOMM_OK
+               : KVCOMM_EHIP;
 }
 
 }  // namespace kvc

@@ -89,12 +89,15 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const lds_byte *a0, const lds
 // inserts no wait of its own before later LDS reads (it would wait for ALL outstanding loads ahead of the
 // first transposing read and so serialise the prefetch).  Ordering is explicit instead: tile_barrier()
 // waits for the loads (vmcnt) and synchronises the block before anybody reads what they wrote.
-// M0 is a reserved register that the compiler itself only ever sets immediately before an instruction
-// that consumes it, so overwriting it here disturbs nothing (nothing else in this file uses it).
+// M0 is listed as clobbered, so the compiler re-forms it for any instruction of its own that needs it.
+// (clang warns about any reserved register in a clobber list; for M0, which it only ever sets immediately
+// before the instruction that reads it, the declaration is exactly what is meant.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16_sbase(const unsigned char *base, uint32_t voff, const lds_byte *dst)
 {
     const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory", "m0");
 }
 
 template <int I, int N, class F>
@@ -113,8 +116,9 @@ template <int OFF>
 __device__ __forceinline__ void dma16_sbase_at(const unsigned char *base, uint32_t voff, uint32_t dst_base)
 {
     asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 : : "v"(voff), "s"(base), "s"(dst_base), "n"(OFF) : "memory", "scc");
+                 : : "v"(voff), "s"(base), "s"(dst_base), "n"(OFF) : "memory", "scc", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int D, int NW, int QB, int WPE>
 __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParams p)
@@ -657,12 +661,11 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         const int64_t rows = (int64_t)p.L * model->n_q_heads * tq;
         const unsigned n_blocks = (unsigned)((rows + 3) / 4);
         switch (D) {
-            case 64: hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(n_blocks), dim3(256), 0, s, p); break;
-            case 128: hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(n_blocks), dim3(256), 0, s, p); break;
-            case 256: hipLaunchKernelGGL(attn_f32_kernel<256>, dim3(n_blocks), dim3(256), 0, s, p); break;
+            case 64: return launch(attn_f32_kernel<64>, dim3(n_blocks), dim3(256), 0, s, p);
+            case 128: return launch(attn_f32_kernel<128>, dim3(n_blocks), dim3(256), 0, s, p);
+            case 256: return launch(attn_f32_kernel<256>, dim3(n_blocks), dim3(256), 0, s, p);
             default: return KVCOMM_EUNSUPPORTED;
         }
-        return launch_status();
     }
 
     // The direct loads address a row group as a 64-bit scalar base plus an unsigned 32-bit per-lane byte
@@ -679,10 +682,9 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
     p.n_row_tiles = (p.G * tq + bm - 1) / bm;
     const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
     switch (D) {
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<64, NW, QB, WPE>), dim3(n_blocks), dim3(64 * NW), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((attn_mfma_kernel<128, NW, QB, WPE>), dim3(n_blocks), dim3(64 * NW), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((attn_mfma_kernel<256, 4, 1, 1>), dim3(n_blocks), dim3(256), 0, s, p); break;
+        case 64: return launch(attn_mfma_kernel<64, NW, QB, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 128: return launch(attn_mfma_kernel<128, NW, QB, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 256: return launch(attn_mfma_kernel<256, 4, 1, 1>, dim3(n_blocks), dim3(256), 0, s, p);
         default: return KVCOMM_EUNSUPPORTED;
     }
-    return launch_status();
 }

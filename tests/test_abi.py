@@ -190,25 +190,62 @@ def test_compressed_deviation_argument_errors(lib):
     assert a8(weights=None) == EINVAL
 
 
+def test_compressed_batch_argument_errors(lib):
+    m = _model()
+    parr = (ctypes.c_void_p * 2)(0x2000, 0x3000)
+    larr = (ctypes.c_int32 * 2)(16, 16)
+    good = (ctypes.c_float * 2)(2.0 ** -10, 2.0 ** -9)
+    bad = (ctypes.c_float * 2)(2.0 ** -10, 0.3)
+    tiny = (ctypes.c_float * 2)(2.0 ** -10, 2.0 ** -130)      # a subnormal power of two has no exponent to pass on
+
+    def job(sk=good, sv=good, out=0x6000, slots=16, weights=0x4000):
+        return binding._CAlignQ8Job(_tensor(), _tensor(0x5000), _tensor(out), _tensor(out + 0x1000), 16, 64, parr, parr,
+                                    larr, None, sk, sv, 2, weights, slots)
+
+    def call(jobs, layout=None):
+        arr = (binding._CAlignQ8Job * max(len(jobs), 1))(*jobs)
+        return lib.kvcomm_align_kv_q8_batch(ctypes.byref(m), 0, layout or _tensor(None, st=128), arr, len(jobs), None)
+
+    assert call([]) == EINVAL
+    assert call([job()] * 9) == EUNSUPPORTED
+    assert call([job(), job(sk=bad, out=0x8000)]) == EINVAL
+    assert call([job(sv=tiny)]) == EINVAL
+    assert call([job(sk=None)]) == EINVAL
+    assert call([job(slots=3)]) == EINVAL
+    assert call([job(), job()]) == EINVAL                       # both jobs write the same rows
+    assert call([job()], layout=_tensor(None, st=24)) == EINVAL
+    assert call([job(), job(out=0x8000)]) != EINVAL
+
+
 def test_batch_argument_errors(lib):
     m = _model()
     parr = (ctypes.c_void_p * 40)(*[0x2000 + 0x100 * i for i in range(40)])
     larr = (ctypes.c_int32 * 40)(*[16] * 40)
 
-    def ajob(n_anchors=2, seg_len=16, weights=0x4000):
-        return binding._CAlignJob(_tensor(), _tensor(0x5000), _tensor(0x6000), _tensor(0x7000), seg_len, 64, parr, parr,
-                                  larr, None, n_anchors, weights)
+    def ajob(n_anchors=2, seg_len=16, weights=0x4000, out=0x6000, slots=16, gran_slots=None):
+        return binding._CAlignJob(_tensor(), _tensor(0x5000), _tensor(out), _tensor(out + 0x1000), seg_len, 64, parr, parr,
+                                  larr, None, n_anchors, weights, slots)
 
-    def acall(jobs):
+    def acall(jobs, gran=0):
         arr = (binding._CAlignJob * max(len(jobs), 1))(*jobs)
-        return lib.kvcomm_align_kv_batch(ctypes.byref(m), 0, _tensor(None), arr, len(jobs), None)
+        return lib.kvcomm_align_kv_batch(ctypes.byref(m), gran, _tensor(None), arr, len(jobs), None)
 
     assert acall([]) == EINVAL
     assert acall([ajob()] * 9) == EUNSUPPORTED                     # more than KVCOMM_MAX_BATCH jobs
-    assert acall([ajob(), ajob(seg_len=0)]) == EINVAL
-    assert acall([ajob(), ajob(weights=None)]) == EINVAL
-    assert acall([ajob(n_anchors=40), ajob(n_anchors=40)]) == EUNSUPPORTED   # 80 selected anchors in one launch
+    assert acall([ajob(), ajob(seg_len=0, out=0x8000)]) == EINVAL
+    assert acall([ajob(), ajob(weights=None, out=0x8000)]) == EINVAL
+    assert acall([ajob(n_anchors=40), ajob(n_anchors=40, out=0x8000)]) == EUNSUPPORTED   # 80 selected anchors in one launch
     assert lib.kvcomm_align_kv_batch(ctypes.byref(m), 0, _tensor(None), None, 1, None) == EINVAL
+    # a job's weight buffer must have the rows its own segment length asks for (a prefix segment that borrows a
+    # placeholder's per-token weights of another length is refused; per-segment weights fit any length)
+    assert acall([ajob(slots=15)]) == EINVAL
+    assert acall([ajob(), ajob(out=0x8000, slots=1)]) == EINVAL
+    assert acall([ajob(slots=1)], gran=2) != EINVAL
+    assert acall([ajob(slots=16)], gran=2) == EINVAL
+    assert acall([ajob(slots=2 * 2 * 16)], gran=1) != EINVAL
+    # two jobs that write the same rows
+    assert acall([ajob(), ajob()]) == EINVAL
+    assert acall([ajob(), ajob(out=0x6800)]) == EINVAL
 
     def wjob(n_anchors=2, seg_len=16, weights=0x4000):
         return binding._CWeightsJob(_tensor(), seg_len, parr, larr, n_anchors, weights, None, None)
@@ -241,6 +278,46 @@ def _align(lib, m, gran=0, seg_len=16, ptrs=(0x2000,), lens=(16,), weights=0x400
     return lib.kvcomm_align_kv(ctypes.byref(m), gran, bk or _tensor(), _tensor(0x5000), seg_len, parr, parr,
                                _tensor(None), larr, A, weights, 64, aarr, out or _tensor(0x6000), _tensor(0x7000),
                                None)
+
+
+def test_align_aliasing_rules(lib):
+    """An output may be exactly its base tensor (in place); any other sharing of bytes with another tensor of the
+    call is an argument error found on the host.  (Every call that passes the checks here would launch; the
+    accepted cases therefore use status != EINVAL on a machine without a GPU.)"""
+    m = _model()
+    parr = (ctypes.c_void_p * 1)(0x2000)
+    larr = (ctypes.c_int32 * 1)(16)
+
+    def call(bk=0x1000, bv=0x5000, ok=0x6000, ov=0x7000, dk=0x2000, dv=0x3000, w=0x4000, ok_t=None, layout=None):
+        pk, pv = (ctypes.c_void_p * 1)(dk), (ctypes.c_void_p * 1)(dv)
+        return lib.kvcomm_align_kv(ctypes.byref(m), 0, _tensor(bk), _tensor(bv), 16, pk, pv, layout or _tensor(None), larr,
+                                   1, w, 64, None, ok_t or _tensor(ok), _tensor(ov), None)
+
+    assert call(ok=0x1000 + 0x800) == EINVAL            # out_k starts inside base_k's first block
+    assert call(ok=0x1000 - 0x800) == EINVAL            # ... or ends inside it
+    assert call(ok=0x5000 + 0x10) == EINVAL             # out_k over base_v
+    assert call(ov=0x1000) == EINVAL                    # out_v exactly base_k: only the own base may be shared
+    assert call(ok=0x6000, ov=0x6000) == EINVAL         # the two outputs on each other
+    assert call(ok=0x6000, ov=0x6800) == EINVAL
+    assert call(ok=0x2000 + 0x40) == EINVAL             # out_k over the anchor's key deviations
+    assert call(ov=0x3000 - 0x40) == EINVAL             # out_v over its value deviations
+    assert call(ok=0x4000 - 0xfc0) == EINVAL            # out_k's last bytes over the weights
+    # same pointer, other strides: not the in-place case
+    assert call(ok_t=_tensor(0x1000, st=256)) == EINVAL
+    # a block of out_k that lands on a LATER block of base_k (other layer / head), same strides
+    assert call(ok=0x1000 + (1 << 16) * 2 + 0x100) == EINVAL
+    assert call(ok=0x1000 + (1 << 20) * 2 - 0x100) == EINVAL
+    # other strides than base_k's (blocks at +0, +0x10000, +0x100000, +0x110000 bytes): the sorted-interval path
+    assert call(ok_t=binding._CTensor(0x8000, 1 << 19, 1 << 15, 128)) != EINVAL       # touches nothing
+    assert call(ok_t=binding._CTensor(0x11000, 1 << 19, 1 << 15, 128)) == EINVAL      # its block (0, 1) is base_k's (0, 1)
+    assert call(ok_t=binding._CTensor(0x101000 + 0x800, 1 << 19, 1 << 15, 128)) == EINVAL   # its (1, 0) ends in base_k's (1, 0)
+    # accepted: disjoint tensors, and the in-place update
+    assert call() != EINVAL
+    assert call(ok=0x1000, ov=0x5000) != EINVAL
+    # an anchor that is too short is never read, so it may lie anywhere
+    short = (ctypes.c_int32 * 1)(8)
+    assert lib.kvcomm_align_kv(ctypes.byref(m), 0, _tensor(), _tensor(0x5000), 16, parr, parr, _tensor(None), short, 1,
+                               0x4000, 64, None, _tensor(0x2000), _tensor(0x7000), None) != EINVAL
 
 
 def test_align_argument_errors(lib):

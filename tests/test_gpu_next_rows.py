@@ -437,6 +437,100 @@ def test_compressed_align_full_size_rate_inputs():
     check_close(f(ov), rv, w.dtype, "V^ q8 full")
 
 
+def test_quantize_nan_infinity_and_saturation():
+    """NaN -> the format's NaN code 0x7f; +-infinity, +-448 * scale and anything beyond saturate at +-448
+    (codes 0x7e / 0xfe); the largest value that still rounds below the bound keeps its own code."""
+    say("quantize NaN / inf / saturation")
+    for w in (SMALL_F32, SMALL_BF16):
+        model = hotpath.model_of(w)
+        scale = 2.0 ** -10
+        x = torch.zeros((w.n_layers, w.n_kv_heads, 9, w.head_dim), dtype=w.dtype, device=DEV)
+        special = [float("nan"), -float("nan"), float("inf"), -float("inf"), 448.0 * scale, -448.0 * scale,
+                   480.0 * scale, -1e30, 416.0 * scale, 432.0 * scale, 1e-30, 464.0 * scale]
+        x[0, 0, 3, :len(special)] = torch.tensor(special, dtype=torch.float32).to(w.dtype)
+        x[-1, -1, 8, -len(special):] = torch.tensor(special, dtype=torch.float32).to(w.dtype)
+        q = kv.kvcomm_quantize_deltas(model, x, scale)
+        torch.cuda.synchronize()
+        got, want = q.cpu().numpy(), oracle.quantize(to_np(x), scale)
+        assert np.array_equal(got[0, 0, 3, :len(special)], want[0, 0, 3, :len(special)]), (got[0, 0, 3, :12], want[0, 0, 3, :12])
+        assert np.array_equal(got[-1, -1, 8, -len(special):], want[-1, -1, 8, -len(special):])
+        assert list(got[0, 0, 3, :8]) == [0x7f, 0x7f, 0x7e, 0xfe, 0x7e, 0xfe, 0x7e, 0xfe]
+        zero_both = ((got & 0x7f) == 0) & ((want & 0x7f) == 0)
+        assert np.all((got == want) | zero_both)
+
+
+def test_compressed_batch_equals_single_calls_and_oracle():
+    """kvcomm_align_kv_q8_batch over segments of mixed length, pool size and recording offsets, written into
+    one agent cache: bit-identical to per-segment kvcomm_align_kv_q8 calls, and equal to the oracle's update
+    on the stored (decoded) values."""
+    say("align q8 batch")
+    base = scaled(SMALL_BF16, n_layers=3, n_kv_heads=2, n_q_heads=4, anchor_delta_choices=(16, 64, 100))
+    shapes = [(70, 5), (203, 3), (33, 8)]
+    model = hotpath.model_of(base)
+    total = sum(s for s, _ in shapes)
+    cache_k = torch.zeros((base.n_layers, base.n_kv_heads, 16 + total, base.head_dim), dtype=base.dtype, device=DEV)
+    cache_v = torch.zeros_like(cache_k)
+    ref_k, ref_v = torch.zeros_like(cache_k), torch.zeros_like(cache_k)
+    jobs, p0, per_seg = [], 16, []
+    for j, (S, A) in enumerate(shapes):
+        w = scaled(base, seg_len=S, n_anchors=A, anchor_lens=(203,) * A, seed=40 + j)   # one capacity: one layout
+        seg = workloads.make_segment(w, 0, j, DEV)
+        sk = [2.0 ** -(9 + (a % 3)) for a in range(A)]
+        sv = [2.0 ** -10] * A
+        qk = [kv.kvcomm_quantize_deltas(model, a, s) for a, s in zip(seg.anchor_dk, sk)]
+        qv = [kv.kvcomm_quantize_deltas(model, a, s) for a, s in zip(seg.anchor_dv, sv)]
+        wts, _, _ = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len)
+        jobs.append(dict(base_k=seg.base_k, base_v=seg.base_v, anchor_dk8=qk, anchor_dv8=qv, scale_k=sk, scale_v=sv,
+                         weights=wts, delta_pos=seg.delta_pos, anchor_delta_pos=seg.anchor_delta_pos,
+                         anchor_len=seg.anchor_len, out_k=cache_k[:, :, p0:p0 + S], out_v=cache_v[:, :, p0:p0 + S]))
+        kv.kvcomm_align_kv_q8(model, seg.base_k, seg.base_v, qk, qv, sk, sv, wts, seg.delta_pos,
+                              ref_k[:, :, p0:p0 + S], ref_v[:, :, p0:p0 + S], seg.anchor_len, seg.anchor_delta_pos)
+        per_seg.append((w, seg, sk, sv, p0))
+        p0 += S
+    kv.kvcomm_align_kv_q8_batch(model, jobs)
+    torch.cuda.synchronize()
+    assert torch.equal(cache_k, ref_k) and torch.equal(cache_v, ref_v)
+    for w, seg, sk, sv, p0 in per_seg:
+        S = w.seg_len
+        dk = [oracle.dequantize(oracle.quantize(to_np(a), s), s) for a, s in zip(seg.anchor_dk, sk)]
+        dv = [oracle.dequantize(oracle.quantize(to_np(a), s), s) for a, s in zip(seg.anchor_dv, sv)]
+        bk, anc = oracle_inputs(seg)
+        dist, sel = oracle.distances(bk, anc, 0)
+        wo, _ = oracle.weights(dist, sel, 1.0)
+        rk, rv = oracle.align(bk, to_np(seg.base_v), dk, dv, wo, seg.delta_pos, w.rope_theta, anc_delta=seg.anchor_delta_pos)
+        check_close(to_np(cache_k[:, :, p0:p0 + S]), rk, w.dtype, "K^ q8 batch")
+        check_close(to_np(cache_v[:, :, p0:p0 + S]), rv, w.dtype, "V^ q8 batch")
+    assert float(cache_k[:, :, :16].abs().max()) == 0.0      # rows outside the segments' slots untouched
+    # a job whose output overlaps another job's is refused
+    jobs[1]["out_k"] = jobs[0]["out_k"]
+    with pytest.raises(kv.KVCommError):
+        kv.kvcomm_align_kv_q8_batch(model, jobs)
+
+
+def test_align_refuses_partial_overlap_on_device_tensors():
+    """The aliasing rule of the boundary on real tensors: in place is fine, a shifted view of the base is not."""
+    say("align aliasing")
+    w = SMALL_BF16
+    model = hotpath.model_of(w)
+    seg = workloads.make_segment(w, 0, 0, DEV)
+    wts, _, _ = kv.kvcomm_anchor_weights(model, seg.base_k, seg.anchor_k, seg.anchor_len)
+    big_k = torch.zeros((w.n_layers, w.n_kv_heads, w.seg_len + 8, w.head_dim), dtype=w.dtype, device=DEV)
+    big_v = torch.zeros_like(big_k)
+    big_k[:, :, :w.seg_len], big_v[:, :, :w.seg_len] = seg.base_k, seg.base_v
+    args = (seg.anchor_dk, seg.anchor_dv, wts, seg.delta_pos)
+    want_k, want_v = torch.empty_like(seg.base_k), torch.empty_like(seg.base_v)
+    kv.kvcomm_align_kv(model, seg.base_k, seg.base_v, *args, want_k, want_v)
+    bk, bv = big_k[:, :, :w.seg_len], big_v[:, :, :w.seg_len]
+    with pytest.raises(kv.KVCommError) as e:
+        kv.kvcomm_align_kv(model, bk, bv, *args, big_k[:, :, 8:], bv)        # out_k = base_k shifted by 8 tokens
+    assert e.value.status == -1
+    with pytest.raises(kv.KVCommError):
+        kv.kvcomm_align_kv(model, bk, bv, *args, bv, bk)                     # outputs swapped onto the other base
+    kv.kvcomm_align_kv(model, bk, bv, *args, bk, bv)                         # in place
+    torch.cuda.synchronize()
+    assert torch.equal(bk, want_k) and torch.equal(bv, want_v)
+
+
 def test_whole_step_under_hip_graph_capture_and_replay():
     """The library only enqueues kernels (no allocation, copy or memset), so a caller can record a whole
     reuse step of an agent into a HIP graph.  Every replay, with eager work and synchronisations between
