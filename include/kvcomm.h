@@ -120,6 +120,32 @@ int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, float tempera
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* --------------------------------------------------------------------------------------
+ * kvcomm_anchor_weights for callers that cannot allocate device memory or size a workspace:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results (bit for bit) and errors as kvcomm_anchor_weights, without the workspace:
+ * the partial sums live in a fixed array of KVCOMM_STATIC_SCRATCH_BYTES that is part of the
+ * library image (each GPU that runs the library holds one copy until the process ends).  The
+ * call allocates and frees nothing.  A request whose kvcomm_anchor_weights_workspace() exceeds
+ * the array returns KVCOMM_EWORKSPACE and launches nothing (16 MiB covers every per-token and
+ * per-segment request of up to 32768 tokens and 64 anchors; per-(layer, head, token) weights
+ * need 8 bytes per layer, head, token and anchor and fit only for short segments).
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different
+ * streams, different host threads) race on it and must be ordered by the caller.  The array's
+ * contents after a call are undefined; no call relies on what an earlier one left.  The first
+ * call on a GPU looks up the array's address (hipGetSymbolAddress); make that call outside
+ * stream capture.                                                                         */
+#define KVCOMM_STATIC_SCRATCH_BYTES (16u << 20)
+
+size_t kvcomm_anchor_weights_static_capacity(void);   /* = KVCOMM_STATIC_SCRATCH_BYTES */
+
+int kvcomm_anchor_weights_static(const kvcomm_model *model, int32_t gran, float temperature,
+                                 kvcomm_tensor seg_base_k, int32_t seg_len,
+                                 const void *const *anchor_base_k, kvcomm_tensor anchor_layout,
+                                 const int32_t *anchor_len, int32_t n_anchors,
+                                 float *weights_out, int32_t *nearest_out, int32_t *selected_out,
+                                 void *stream);
+
+/* --------------------------------------------------------------------------------------
  * Offset approximation fused with positional alignment (Eq. "ph_update"; with the
  * prefix segment's tensors and the placeholder's weights it is Eq. "pf_update"):
  *   out_k[l,h,t,:] = R(delta_pos) base_k[l,h,t,:]

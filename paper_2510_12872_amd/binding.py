@@ -109,6 +109,11 @@ def load_library():
     lib.kvcomm_anchor_weights.argtypes = [mp, i32, f32, _CTensor, i32, ctypes.POINTER(vp), _CTensor,
                                           ctypes.POINTER(i32), i32, vp, vp, vp, vp, sz, vp]
     lib.kvcomm_anchor_weights.restype = ctypes.c_int
+    lib.kvcomm_anchor_weights_static_capacity.argtypes = []
+    lib.kvcomm_anchor_weights_static_capacity.restype = sz
+    lib.kvcomm_anchor_weights_static.argtypes = [mp, i32, f32, _CTensor, i32, ctypes.POINTER(vp), _CTensor,
+                                                 ctypes.POINTER(i32), i32, vp, vp, vp, vp]
+    lib.kvcomm_anchor_weights_static.restype = ctypes.c_int
     lib.kvcomm_align_kv.argtypes = [mp, i32, _CTensor, _CTensor, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     _CTensor, ctypes.POINTER(i32), i32, vp, i32, ctypes.POINTER(i32),
                                     _CTensor, _CTensor, vp]
@@ -218,6 +223,25 @@ def kvcomm_anchor_weights(model, seg_base_k, anchor_base_k, anchor_len=None, tem
                                      weights_out.data_ptr(), nearest_out.data_ptr(), selected_out.data_ptr(),
                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                      _stream_ptr(stream)))
+    return weights_out, nearest_out, selected_out
+
+
+def kvcomm_anchor_weights_static_capacity():
+    return int(load_library().kvcomm_anchor_weights_static_capacity())
+
+
+def kvcomm_anchor_weights_static(model, seg_base_k, anchor_base_k, weights_out, nearest_out, selected_out,
+                                 anchor_len=None, temperature=1.0, gran=W_TOKEN, stream=None):
+    """kvcomm_anchor_weights without a workspace argument (the library's fixed scratch array).  The caller
+    passes every output; nothing is allocated here or in the library."""
+    lib = load_library()
+    ptrs, layout, lens = _anchor_args(anchor_base_k, anchor_len, model.dtype, "anchor_base_k")
+    _check(lib.kvcomm_anchor_weights_static(ctypes.byref(model.c()), gran, float(temperature),
+                                            _desc(seg_base_k, model.dtype, "seg_base_k"), seg_base_k.shape[2], ptrs,
+                                            layout, lens, len(anchor_base_k), weights_out.data_ptr(),
+                                            None if nearest_out is None else nearest_out.data_ptr(),
+                                            None if selected_out is None else selected_out.data_ptr(),
+                                            _stream_ptr(stream)))
     return weights_out, nearest_out, selected_out
 
 

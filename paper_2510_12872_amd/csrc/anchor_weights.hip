@@ -18,7 +18,14 @@
 // similarities).  Both reuse the two-stage structure and the finalize kernels.
 #include <math.h>
 
+#include <mutex>
+
 #include "kvcomm_device.h"
+
+// Partial sums of kvcomm_anchor_weights_static: one array per GPU that has loaded the library, kept
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// kernels receive the address that call returns.
+static __device__ __align__(256) unsigned char scratch[KVCOMM_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -727,4 +734,52 @@ extern "C" int kvcomm_anchor_weights(const kvcomm_model *model, int32_t gran, fl
     return kvcomm_anchor_weights_rule(model, gran, KVCOMM_RULE_L2_SOFTMAX, temperature, seg_base_k, seg_len,
                                       anchor_base_k, anchor_layout, anchor_len, n_anchors, weights_out, nearest_out,
                                       selected_out, workspace, workspace_bytes, stream);
+}
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once per GPU
+
+// Address of the current device's copy of `scratch` (every GPU holds its own copy at its own address).
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVCOMM_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KVCOMM_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVCOMM_OK;
+}
+
+}  // namespace
+
+extern "C" size_t kvcomm_anchor_weights_static_capacity(void) { return KVCOMM_STATIC_SCRATCH_BYTES; }
+
+extern "C" int kvcomm_anchor_weights_static(const kvcomm_model *model, int32_t gran, float temperature,
+                                            kvcomm_tensor seg_base_k, int32_t seg_len,
+                                            const void *const *anchor_base_k, kvcomm_tensor anchor_layout,
+                                            const int32_t *anchor_len, int32_t n_anchors, float *weights_out,
+                                            int32_t *nearest_out, int32_t *selected_out, void *stream)
+{
+    // Size first: a request that does not fit is refused before anything else is looked at.
+    int st = check_model(model);
+    if (st) return st;
+    if ((st = check_gran(gran))) return st;
+    if (seg_len <= 0 || n_anchors <= 0) return KVCOMM_EINVAL;
+    if (n_anchors > KVCOMM_MAX_ANCHORS) return KVCOMM_EUNSUPPORTED;
+    const size_t need = kvcomm_anchor_weights_workspace(model, seg_len, n_anchors, gran);
+    if (need > KVCOMM_STATIC_SCRATCH_BYTES) return KVCOMM_EWORKSPACE;
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws))) return st;
+    // Nothing in the array has to start at zero: the distance kernel writes every partial sum that the
+    // finalize kernel reads, whatever an earlier call left behind.
+    return kvcomm_anchor_weights(model, gran, temperature, seg_base_k, seg_len, anchor_base_k, anchor_layout,
+                                 anchor_len, n_anchors, weights_out, nearest_out, selected_out, ws,
+                                 KVCOMM_STATIC_SCRATCH_BYTES, stream);
 }

@@ -217,6 +217,36 @@ def test_compressed_batch_argument_errors(lib):
     assert call([job(), job(out=0x8000)]) != EINVAL
 
 
+def test_static_scratch_entry_point_argument_errors(lib):
+    """The entry point without a workspace argument refuses what does not fit its fixed array before it
+    looks at anything else, and validates like kvcomm_anchor_weights otherwise."""
+    m = _model(n_layers=32, n_kv_heads=8, n_q_heads=32)
+    cap = lib.kvcomm_anchor_weights_static_capacity()
+    assert cap == 16 << 20
+
+    def call(seg_len=16, A=2, gran=0, tau=1.0, weights=0x4000, model=m):
+        parr = (ctypes.c_void_p * A)(*[0x2000 + 0x1000 * i for i in range(A)])
+        larr = (ctypes.c_int32 * A)(*[seg_len] * A)
+        return lib.kvcomm_anchor_weights_static(ctypes.byref(model), gran, tau, _tensor(), seg_len, parr, _tensor(None),
+                                                larr, A, weights, None, None, None)
+
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 1024, 64, 0) <= cap
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 2048, 16, 0) <= cap
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), 32768, 64, 0) <= cap    # the per-token cut adapts
+    big = (65536, 64, 0)
+    assert lib.kvcomm_anchor_weights_workspace(ctypes.byref(m), *big) > cap
+    assert call(seg_len=big[0], A=big[1], gran=big[2]) == EWORKSPACE
+    assert call(seg_len=2048, A=8, gran=1) == EWORKSPACE         # one partial per (layer, head, token, anchor): 32 MiB
+    assert call(seg_len=0) == EINVAL
+    assert call(gran=7) == EINVAL
+    assert call(A=0) == EINVAL
+    assert call(A=65) == EUNSUPPORTED
+    assert call(model=_model(head_dim=80)) == EUNSUPPORTED
+    # what fits goes on to the checks of kvcomm_anchor_weights itself, still on the host
+    assert call(tau=0.0) in (EINVAL, -4)
+    assert call(weights=None) in (EINVAL, -4)
+
+
 def test_batch_argument_errors(lib):
     m = _model()
     parr = (ctypes.c_void_p * 40)(*[0x2000 + 0x100 * i for i in range(40)])
