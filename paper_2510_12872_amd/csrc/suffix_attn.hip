@@ -53,17 +53,12 @@ struct AttnParams {
 };
 
 // ------------------------------------------------------------------------------- bf16 MFMA
-#ifndef KVC_ATTN_QB
-#define KVC_ATTN_QB 1
-#endif
 #ifndef KVC_ATTN_WPE
 #define KVC_ATTN_WPE 2
 #endif
 #ifndef KVC_ATTN_NW
 #define KVC_ATTN_NW 8  // measured: 2 % faster than two blocks of 4 per CU (every K/V tile enters LDS once per CU)
 #endif
-
-constexpr float kLazyLog2 = 8.f;  // the softmax reference maximum lags the true one by at most 2^8
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -100,6 +95,9 @@ __device__ __forceinline__ void dma16_sbase(const unsigned char *base, uint32_t 
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(m0) : "memory", "m0");
 }
 
+template <int V>
+using template_int = std::integral_constant<int, V>;
+
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F &&f)
 {
@@ -120,13 +118,12 @@ __device__ __forceinline__ void dma16_sbase_at(const unsigned char *base, uint32
 }
 #pragma clang diagnostic pop
 
-template <int D, int NW, int QB, int WPE>
+template <int D, int NW, int WPE>
 __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParams p)
 {
-    constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T
+    constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T; also the MFMAs of O^T += V^T P^T per sub-step
     constexpr int NDB = D / 32;      // 32-row blocks of O^T
-    constexpr int MW = 32 * QB;      // query rows per wavefront: QB blocks of 32
-    constexpr int BM = MW * NW;      // query rows per block
+    constexpr int BM = 32 * NW;      // query rows per block (32 per wavefront)
     constexpr int RW = 64 / NW;      // key rows of a 64-key group that one wavefront loads
     constexpr int KCH = D / 8;       // 16-byte chunks per K / V row
     constexpr int ROWB = D * 2;      // bytes per K / V row
@@ -162,18 +159,16 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     const bf16_t *kb_ = static_cast<const bf16_t *>(p.k) + l * p.s_k.layer + hkv * p.s_k.head;
     const bf16_t *vb_ = static_cast<const bf16_t *>(p.v) + l * p.s_v.layer + hkv * p.s_v.head;
 
-    // This lane's query column in each of the wavefront's QB blocks: row r = i * G + g of the
-    // (layer, kv head) group.
-    int qi[QB], hq[QB];
-    bf16x8 qf[QB][NKS];
+    // This lane's query column: row r = i * G + g of the (layer, kv head) group.
+    int qi;
+    bf16x8 qf[NKS];
+    {
+        const int r_row = rt * BM + wave * 32 + n;
+        qi = min(r_row / p.G, p.tq - 1);
+        const int hq = hkv * p.G + r_row % p.G;
+        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)(uint32_t)hq * p.s_q.head + (int64_t)(uint32_t)qi * p.s_q.token;
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {
-        const int r_row = rt * BM + wave * MW + b * 32 + n;
-        qi[b] = min(r_row / p.G, p.tq - 1);
-        hq[b] = hkv * p.G + r_row % p.G;
-        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)(uint32_t)hq[b] * p.s_q.head + (int64_t)(uint32_t)qi[b] * p.s_q.token;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[b][ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
     }
 
     // Every wavefront of the block walks the same tiles (one barrier per 64-key tile); the causal
@@ -184,17 +179,11 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     const int n_sub = 2 * n_tiles;
     const int sub_unmasked = (p.n_ctx + wg_imin + 1) / 32;  // sub-steps [0, sub_unmasked) are visible to all queries
 
-    f32x16 o[QB][NDB];
-    float m[QB], lsum[QB];
+    f32x16 o[NDB];
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {
-        m[b] = -INFINITY;
-        lsum[b] = 0.f;
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) o[b][db][j] = 0.f;
-    }
+        for (int j = 0; j < 16; ++j) o[db][j] = 0.f;
 
     // ---- global -> LDS direct loads (global_load_lds_dwordx4): lane i of a wavefront fills the
     // 16-byte LDS chunk (base + i); the swizzle is applied by choosing which global chunk it fetches.
@@ -218,7 +207,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     const unsigned char *kbytes = reinterpret_cast<const unsigned char *>(kb_);
     const unsigned char *vbytes = reinterpret_cast<const unsigned char *>(vb_);
 
-    // 64 keys starting at key0 (a multiple of 32) -> K ring; its two halves are h0 = key0/32 and h0+1.
+    // 64 keys starting at key0 (a multiple of 64) -> K ring; its two halves are h0 = key0/32 and h0+1.
     // A half outside [0, n_sub) is skipped.  The lower NW/2 wavefronts fill the first half, the rest the second.
     // General form (prologue and the last tiles): rows past the cache end re-read the last row; such
     // rows are never unmasked.  The row base is clamped on the scalar unit and a lane whose row would
@@ -233,7 +222,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     };
     auto load_k64 = [&](int key0) __attribute__((always_inline)) {
         const int h = key0 / 32 + wave / (NW / 2);
-        if (h < 0 || h >= n_sub) return;  // wavefront-uniform
+        if (h >= n_sub) return;  // wavefront-uniform
         const int rbase = (wave % (NW / 2)) * RW;
 #pragma unroll
         for (int it = 0; it < LPT; ++it)
@@ -241,6 +230,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
                       kring + (h & 3) * HALFB + (rbase + it * RPL) * ROWB);
     };
     auto load_v64 = [&](int tile) __attribute__((always_inline)) {
+        if (tile >= n_tiles) return;
 #pragma unroll
         for (int it = 0; it < LPT; ++it)
             load_rows(vbytes, p.s_v.token, v_row_bytes, 64 * tile + wave * RW + it * RPL, ld_voff[it],
@@ -248,16 +238,17 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     };
     // Steady state (all rows exist, no half is skipped): the same loads from two running row pointers,
     // so that a load costs one 64-bit scalar add instead of a 64-bit multiply, and with M0 formed from
-    // a per-wavefront LDS base plus a literal.  kp / vp point at this wavefront's next row to load.
+    // a per-wavefront LDS base plus a literal.  kp / vp point at this wavefront's next row to load:
+    // during tile t the K halves 2t+4, 2t+5 (keys 64t+128 ...) and V tile t+1.
     const int64_t k_rpl = (int64_t)RPL * p.s_k.token * 2, v_rpl = (int64_t)RPL * p.s_v.token * 2;
     const int64_t k_adv = (int64_t)(64 - LPT * RPL) * p.s_k.token * 2, v_adv = (int64_t)(64 - LPT * RPL) * p.s_v.token * 2;
-    const unsigned char *kp = kbytes + (int64_t)(96 + 32 * (wave / (NW / 2)) + (wave % (NW / 2)) * RW) * p.s_k.token * 2;
+    const unsigned char *kp = kbytes + (int64_t)(128 + 32 * (wave / (NW / 2)) + (wave % (NW / 2)) * RW) * p.s_k.token * 2;
     const unsigned char *vp = vbytes + (int64_t)(64 + wave * RW) * p.s_v.token * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)kring;
     const uint32_t k_rows = lds0 + (wave % (NW / 2)) * RW * ROWB;
-    // K halves 2t+3, 2t+4 (t even) live in slots 3, 0; halves 2t+5, 2t+6 in slots 1, 2
-    const uint32_t kdst_a = __builtin_amdgcn_readfirstlane(k_rows + ((3 + wave / (NW / 2)) & 3) * HALFB);
-    const uint32_t kdst_b = __builtin_amdgcn_readfirstlane(k_rows + ((1 + wave / (NW / 2)) & 3) * HALFB);
+    // t even: halves 2t+4, 2t+5 live in slots 0, 1; t odd: in slots 2, 3
+    const uint32_t kdst_a = __builtin_amdgcn_readfirstlane(k_rows + (0 + wave / (NW / 2)) * HALFB);
+    const uint32_t kdst_b = __builtin_amdgcn_readfirstlane(k_rows + (2 + wave / (NW / 2)) * HALFB);
     const uint32_t vdst = __builtin_amdgcn_readfirstlane(lds0 + 4 * HALFB + wave * RW * ROWB);
     auto load_kv_next = [&](uint32_t kdst, auto vb) __attribute__((always_inline)) {
         constexpr int VB = decltype(vb)::value;  // V buffer, a literal
@@ -293,12 +284,6 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             v_off[db] = row * ROWB + pc * 16 + (col & 7) * 2;
         }
     }
-
-    // ---- phases of one 32-key sub-step u (keys [32u, 32u + 32)).
-    // The two matrix products of a step are interleaved BY HAND with the vector work that runs in
-    // their shadow: each MFMA is followed by a small chunk of independent VALU instructions and a
-    // scheduling barrier pins that order, so the matrix pipe and the vector ALU stay busy together.
-    // LDS operands are fetched two MFMAs ahead.
     auto read_k = [&](const lds_byte *kl, int ks) __attribute__((always_inline)) -> bf16x8 {
         return as_bf16x8(*(const __attribute__((address_space(3))) u32x4 *)(kl + k_off[ks]));
     };
@@ -307,243 +292,220 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         return lds_read_tr_pair(va, va + 8 * ROWB);
     };
 
-    // S^T = K Q^T alone (prologue).
-    auto qk_sub = [&](int u, f32x16 (&s)[QB]) __attribute__((always_inline)) {
-        const lds_byte *kl = kring + (u & 3) * HALFB;
-#pragma unroll
-        for (int b = 0; b < QB; ++b)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) s[b][j] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 a = read_k(kl, ks);
-#pragma unroll
-            for (int b = 0; b < QB; ++b) s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b][ks], s[b], 0, 0, 0);
-        }
-    };
+    // ---- softmax state of this lane's query.
+    // m is the REFERENCE the exponentials are taken against (raw score units), mc = m * scale * log2(e).  It is
+    // a true maximum when it is set, but it is not tracked: a sub-step only checks that its exponentials stayed
+    // in range (their row sum, which is needed anyway, below kOverflow) and re-references the row when they did
+    // not.  Numerator and denominator share the reference, so the result is that of the usual online softmax;
+    // exponentials beyond 1 cost no accuracy in floating point.
+    float m = -INFINITY, mc = 0.f, lsum = 0.f;
+    f32x16 sbuf[2];   // scores of sub-step u live in sbuf[u & 1]
+    u32x4 pbuf[2][2]; // packed bf16 probabilities of sub-step u live in pbuf[u & 1]
 
-    // Mask and running maximum of S(u) (lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4), in chunks:
-    // chunk c of NC folds elements [16c/NC, 16(c+1)/NC) into mx.
-    auto max_chunk = [&](int b, int u, bool masked, f32x16 &s, float &mx, int c, int NC) __attribute__((always_inline)) {
-        const int limit = p.n_ctx + qi[b] - 32 * u;  // last visible key, relative to the sub-step
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            if (j * NC / 16 != c) continue;
-            if (masked) {
-                const int key = 8 * (j >> 2) + 4 * hg + (j & 3);
-                s[j] = key > limit ? -INFINITY : s[j];
-            }
-            mx = fmaxf(mx, s[j]);
-        }
-    };
-    // Closes the maximum: exchange with lane ^ 32 (the other 16 keys of this query) and update the
-    // REFERENCE maximum m that the exponentials are taken against.  The reference only moves when the
-    // true maximum exceeds it by more than 2^kLazyLog2 (scaled, base-2 units), so exponentials stay
-    // below 2^kLazyLog2 -- harmless in fp32 / bf16 -- and O is rescaled on very few sub-steps.  The
-    // result is mathematically the same: numerator and denominator share the reference.
-    // Returns the factor by which O has to be rescaled (exactly 1 if the reference stayed).
-    auto max_finish = [&](int b, float mx) __attribute__((always_inline)) -> float {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        // m == -inf only before the first sub-step, where key 0 makes mx finite
-        const float m_new = (mx - m[b]) * p.scale_log2 > kLazyLog2 ? mx : m[b];
-        const float corr = __builtin_amdgcn_exp2f((m[b] - m_new) * p.scale_log2);
-        m[b] = m_new;
-        lsum[b] *= corr;
-        return corr;
-    };
-    // Exponentials against the reference maximum, packed bf16 B operands, and the row sum taken from
-    // the ROUNDED values (v_dot2_f32_bf16 with ones), so that numerator and denominator agree.
-    auto exp_chunk = [&](f32x16 &s, u32x4 (&pk)[2], float mc, float &rs, int c, int NC) __attribute__((always_inline)) {
+    // Exponentials of elements [16c/NC, 16(c+1)/NC) of s against the reference -> packed bf16 B operands; the row sum
+    // is taken from the ROUNDED values (v_dot2_f32_bf16 with ones) so that numerator and denominator agree.
+    // Lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4 of the sub-step; `limit` is its last visible key.
+    auto exp_chunk = [&](const f32x16 &s, u32x4 (&pk)[2], float &rs, float &e_even, int limit, bool masked, int c, int NC)
+                         __attribute__((always_inline)) {
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             if (j * NC / 16 != c) continue;
-            s[j] = __builtin_amdgcn_exp2f(s[j] * p.scale_log2 - mc);
+            float v = s[j];
+            if (masked) v = 8 * (j >> 2) + 4 * hg + (j & 3) > limit ? -INFINITY : v;
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(v, p.scale_log2, -mc));
             if (j & 1) {
-                const uint32_t pr = pack_bf16x2(s[j - 1], s[j]);
+                const uint32_t pr = pack_bf16x2(e_even, e);
                 pk[j >> 3][(j & 7) >> 1] = pr;
                 rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pr), ones, rs, false);
+            } else {
+                e_even = e;
             }
         }
     };
-    auto rescale = [&](int b, float corr) __attribute__((always_inline)) {
-        // only when the reference of some query of the wavefront moved (rare after the first tiles)
-        if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {
+    // A row whose exponentials left the safe range (or the first sub-step, whose reference is still -inf): take
+    // the true maximum of the sub-step as the new reference if it is larger, rescale what has been accumulated,
+    // and form the exponentials again.  Rare: the reference only ever moves by more than log2(kOverflow).
+    auto rereference = [&](const f32x16 &s, u32x4 (&pk)[2], int limit, bool masked) __attribute__((always_inline)) -> float {
+        float mx = -INFINITY;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) o[b][db][j] *= corr;
+        for (int j = 0; j < 16; ++j) {
+            float v = s[j];
+            if (masked) v = 8 * (j >> 2) + 4 * hg + (j & 3) > limit ? -INFINITY : v;
+            mx = fmaxf(mx, v);
         }
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        const float m_new = fmaxf(m, mx);
+        // m == -inf only in the first sub-step, where key 0 is visible to every query and nothing is accumulated yet
+        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m - m_new) * p.scale_log2);
+        m = m_new;
+        mc = m_new * p.scale_log2;
+        lsum *= corr;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[db][j] *= corr;
+        float rs = 0.f, e_even = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) exp_chunk(s, pk, rs, e_even, limit, masked, c, 4);
+        return rs;
     };
+    constexpr float kOverflow = 1073741824.f;  // 2^30
 
-    // One pipeline step for sub-step u, whose scores s_a already have their maximum folded into m:
-    //   A: S(u+1) = K(u+1) Q^T on the matrix cores  ||  exponentials of S(u) on the vector ALU
-    //   B: O += V(u) P(u) on the matrix cores        ||  mask + running max of S(u+1)
-    //   C: rescale O if that maximum moved (after B, before the next sub-step is added).
-    // With has_next == false only the exponentials and the second product run.
-    // `u4` must equal u & 3 and is a literal at every call site: it fixes the K ring slot and the V
-    // buffer, so every LDS operand address is a per-lane register plus an immediate offset.
-    auto substep = [&](int u, int u4, bool has_next, bool next_masked, f32x16 (&s_a)[QB], f32x16 (&s_b)[QB]) __attribute__((always_inline)) {
-        u32x4 pk[QB][2];
-        float mc[QB], rs[QB];
-#pragma unroll
-        for (int b = 0; b < QB; ++b) {
-            mc[b] = m[b] * p.scale_log2;
-            rs[b] = 0.f;
-        }
-        if (has_next) {
-            const lds_byte *kl = kring + ((u4 + 1) & 3) * HALFB;
-            bf16x8 ka[NKS];
+    // One pipeline step for sub-step u (U4 = u & 3, a literal at every call site, fixes every ring slot and buffer):
+    //   matrix cores:  S(u+2) = K(u+2) Q^T  and  O += V(u) P(u), their MFMAs alternating (two independent chains);
+    //   vector ALU:    P(u+1) = exp2(S(u+1) - reference), spread evenly over the MFMAs.
+    // DO_QK / DO_EXP are false only in the last two sub-steps.  LDS operands are fetched two MFMAs of their own
+    // product ahead; every MFMA + vector chunk is pinned by a scheduling barrier.
+    auto step = [&](int u, auto u4c, auto do_qk_c, auto do_exp_c, auto masked_c) __attribute__((always_inline)) {
+        constexpr int U4 = decltype(u4c)::value;
+        constexpr bool DO_QK = decltype(do_qk_c)::value, DO_EXP = decltype(do_exp_c)::value, MASKED = decltype(masked_c)::value;
+        f32x16 &s_acc = sbuf[U4 & 1];
+        const f32x16 &s_exp = sbuf[(U4 + 1) & 1];
+        const lds_byte *kl = kring + ((U4 + 2) & 3) * HALFB;
+        const lds_byte *vl = vbuf + ((U4 >> 1) & 1) * TILEB + (U4 & 1) * HALFB;
+        const int limit = p.n_ctx + qi - 32 * (u + 1);  // last visible key of S(u+1), relative to its sub-step
+        bf16x8 ka[NKS], va[NKS], pf[2];
+        pf[0] = as_bf16x8(pbuf[U4 & 1][0]);
+        pf[1] = as_bf16x8(pbuf[U4 & 1][1]);
+        if (DO_QK) {
             ka[0] = read_k(kl, 0);
             ka[1] = read_k(kl, 1);
-#pragma unroll
-            for (int b = 0; b < QB; ++b)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) s_b[b][j] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-#pragma unroll
-                for (int b = 0; b < QB; ++b) {
-                    s_b[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[b][ks], s_b[b], 0, 0, 0);
-                    if (b == 0 && ks + 2 < NKS) ka[ks + 2] = read_k(kl, ks + 2);
-                    exp_chunk(s_a[b], pk[b], mc[b], rs[b], ks, NKS);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int b = 0; b < QB; ++b)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) exp_chunk(s_a[b], pk[b], mc[b], rs[b], c, 4);
         }
-        bf16x8 pf[QB][2];
-#pragma unroll
-        for (int b = 0; b < QB; ++b) {
-            lsum[b] += rs[b];
-            pf[b][0] = as_bf16x8(pk[b][0]);
-            pf[b][1] = as_bf16x8(pk[b][1]);
-        }
-
-        const lds_byte *vl = vbuf + ((u4 >> 1) & 1) * TILEB + (u4 & 1) * HALFB;
-        constexpr int NPV = 2 * NDB;
-        bf16x8 va[NPV];
         va[0] = read_v(vl, 0);
         va[1] = read_v(vl, 1);
-        float mx[QB];
+        float rs = 0.f, e_even = 0.f;
 #pragma unroll
-        for (int b = 0; b < QB; ++b) mx[b] = -INFINITY;
+        for (int i = 0; i < NKS; ++i) {
+            if (DO_QK) {
+                if (i == 0) {
+                    f32x16 z;
 #pragma unroll
-        for (int i = 0; i < NPV; ++i) {
-#pragma unroll
-            for (int b = 0; b < QB; ++b) {
-                o[b][i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[b][i / NDB], o[b][i % NDB], 0, 0, 0);
-                if (b == 0 && i + 2 < NPV) va[i + 2] = read_v(vl, i + 2);
-                if (has_next) max_chunk(b, u + 1, next_masked, s_b[b], mx[b], i, NPV);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int j = 0; j < 16; ++j) z[j] = 0.f;
+                    s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0], z, 0, 0, 0);
+                } else {
+                    s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s_acc, 0, 0, 0);
+                }
+                if (i + 2 < NKS) ka[i + 2] = read_k(kl, i + 2);
             }
+            if (DO_EXP) exp_chunk(s_exp, pbuf[(U4 + 1) & 1], rs, e_even, limit, MASKED, 2 * i, 2 * NKS);
+            __builtin_amdgcn_sched_barrier(0);
+            o[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[i / NDB], o[i % NDB], 0, 0, 0);
+            if (i + 2 < NKS) va[i + 2] = read_v(vl, i + 2);
+            if (DO_EXP) exp_chunk(s_exp, pbuf[(U4 + 1) & 1], rs, e_even, limit, MASKED, 2 * i + 1, 2 * NKS);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (has_next) {
-#pragma unroll
-            for (int b = 0; b < QB; ++b) rescale(b, max_finish(b, mx[b]));
+        if (DO_EXP) {
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs < kOverflow)) != 0, 0)) rs = rereference(s_exp, pbuf[(U4 + 1) & 1], limit, MASKED);
+            lsum += rs;
         }
-
     };
     const auto tile_barrier = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's direct loads have landed in LDS
         __syncthreads();                     // ... and everybody else's; what was read in this tile is free
     };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    template_int<0> u0; template_int<1> u1; template_int<2> u2; template_int<3> u3;
 
-    // ---- pipeline over tiles.  During tile t the sub-steps 2t and 2t+1 read K halves 2t+1 and 2t+2
-    // and V tile t; the loads issued at its start (K halves 2t+3, 2t+4 into the slots of halves 2t-1
-    // and 2t, V tile t+1 into the buffer of tile t-1) only overwrite what tile t-1 finished reading.
-    load_k64(-32);  // half 0
-    load_k64(32);   // halves 1, 2
+    // ---- pipeline over tiles.  During tile t the sub-steps 2t and 2t+1 read K halves 2t+2 and 2t+3 and V tile t;
+    // the loads issued at its start (K halves 2t+4, 2t+5 into the slots of halves 2t and 2t+1, V tile t+1 into the
+    // buffer of tile t-1) only overwrite what tile t-1 finished reading.
+    load_k64(0);    // halves 0, 1
+    load_k64(64);   // halves 2, 3
     load_v64(0);
     tile_barrier();
 
-    f32x16 s0[QB], s1[QB];
-    qk_sub(0, s0);
-    const int t_last = n_tiles - 1;
-    // Leading tiles that need no mask in either sub-step (nor in the first sub-step of the next
-    // tile, whose maximum is taken at their end) and whose look-ahead loads stay inside the cache.
-    const int t_safe = p.N >= 224 ? (p.N - 224) / 64 + 1 : 0;  // a tile pair starting at t loads keys up to 64t + 223
-    const int t_plain = max(0, min(min((sub_unmasked - 1) >> 1, t_last), t_safe));
+    // Prologue: S(0) and S(1); the reference of every query from S(0) (key 0 is visible to all); P(0).
+    {
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {  // maximum of sub-step 0; O is still zero, so there is nothing to rescale
-        float mx = -INFINITY;
+        for (int h = 0; h < 2; ++h) {
+            const lds_byte *kl = kring + h * HALFB;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) max_chunk(b, 0, true, s0[b], mx, c, 4);
-        (void)max_finish(b, mx);
+            for (int j = 0; j < 16; ++j) sbuf[h][j] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                sbuf[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(kl, ks), qf[ks], sbuf[h], 0, 0, 0);
+        }
+        lsum = rereference(sbuf[0], pbuf[0], p.n_ctx + qi, true);
     }
-    // Half 0 has no tile before it: every wavefront must have read it before the loads of the first
-    // tile pair (half 4 shares its slot) are issued.
+    // Halves 0 and 1 have no tile before them: every wavefront must have read them before the loads of the
+    // first tile (halves 4 and 5 share their slots) are issued.
     __syncthreads();
+
+    const int t_last = n_tiles - 1;
+    // Leading tiles whose exponentials need no mask and whose look-ahead loads stay inside the cache: a tile pair
+    // starting at t forms the exponentials of sub-steps up to 2t+4 and loads keys up to 64t + 255.
+    const int t_safe = p.N >= 256 ? (p.N - 128) / 64 : 0;
+    const int t_plain = max(0, min(min((sub_unmasked - 1) >> 1, t_last), t_safe));
     // Two tiles (four sub-steps) per trip so that ring slots and buffers are compile-time constants.
-    auto tile_pair = [&](int t, bool clamp, bool masked) __attribute__((always_inline)) {
-        if (clamp) {
-            load_k64(64 * t + 96);
+    auto tile_pair = [&](int t, auto plain) __attribute__((always_inline)) {
+        constexpr bool PLAIN = decltype(plain)::value;
+        using M_ = std::integral_constant<bool, !PLAIN>;
+        if (PLAIN) {
+            load_kv_next(kdst_a, template_int<1>{});  // K halves 2t+4, 2t+5, V tile t+1
+        } else {
+            load_k64(64 * t + 128);
             load_v64(t + 1);
-        } else {
-            load_kv_next(kdst_a, std::integral_constant<int, 1>{});  // K halves 2t+3, 2t+4, V tile t+1
         }
-        substep(2 * t, 0, true, masked, s0, s1);
-        substep(2 * t + 1, 1, true, masked, s1, s0);
+        step(2 * t, u0, T_{}, T_{}, M_{});
+        step(2 * t + 1, u1, T_{}, T_{}, M_{});
         tile_barrier();
-        if (clamp) {
-            load_k64(64 * t + 160);
-            load_v64(t + 2);
+        if (PLAIN) {
+            load_kv_next(kdst_b, template_int<0>{});  // K halves 2t+6, 2t+7, V tile t+2
         } else {
-            load_kv_next(kdst_b, std::integral_constant<int, 0>{});  // K halves 2t+5, 2t+6, V tile t+2
+            load_k64(64 * t + 192);
+            load_v64(t + 2);
         }
-        substep(2 * t + 2, 2, true, masked, s0, s1);
-        substep(2 * t + 3, 3, true, masked, s1, s0);
+        step(2 * t + 2, u2, T_{}, T_{}, M_{});
+        step(2 * t + 3, u3, T_{}, T_{}, M_{});
         tile_barrier();
     };
     int t = 0;
-    for (; t + 2 <= t_plain; t += 2) tile_pair(t, false, false);
-    for (; t + 2 <= t_last; t += 2) tile_pair(t, true, true);
-    if (t < t_last) {  // one more tile with a successor (t is even)
-        load_k64(64 * t + 96);
+    for (; t + 2 <= t_plain; t += 2) tile_pair(t, T_{});
+    for (; t + 2 <= t_last; t += 2) tile_pair(t, F_{});
+    if (t < t_last) {  // two tiles left (t is even): a whole one, then the last
+        load_k64(64 * t + 128);
         load_v64(t + 1);
-        substep(2 * t, 0, true, true, s0, s1);
-        substep(2 * t + 1, 1, true, true, s1, s0);
+        step(2 * t, u0, T_{}, T_{}, T_{});
+        step(2 * t + 1, u1, T_{}, T_{}, T_{});
         tile_barrier();
         ++t;
-        substep(2 * t, 2, true, true, s0, s1);
-        substep(2 * t + 1, 3, false, false, s1, s0);  // the last sub-step has no successor
+        step(2 * t, u2, F_{}, T_{}, T_{});      // S(2t+1) exists already; nothing further to multiply
+        step(2 * t + 1, u3, F_{}, F_{}, T_{});  // the last sub-step only adds its V P
     } else {
-        substep(2 * t, 0, true, true, s0, s1);
-        substep(2 * t + 1, 1, false, false, s1, s0);
+        step(2 * t, u0, F_{}, T_{}, T_{});
+        step(2 * t + 1, u1, F_{}, F_{}, T_{});
     }
 
     // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
-#pragma unroll
-    for (int b = 0; b < QB; ++b) {
+    {
         float ltot;
         {
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum[b]), __float_as_uint(lsum[b]), false, false);
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
             ltot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
         }
         // Row coordinates again, from a freshly read lane id: the compiler then keeps none of the
-        // prologue's address terms alive across the tile loops (the register file is full there).
+        // prologue's address terms alive across the tile loops.
         const int lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-        const int r_row = rt * BM + wave * MW + b * 32 + (lane_e & 31);
-        if (r_row / p.G >= p.tq) continue;
-        const uint32_t qi_e = (uint32_t)(r_row / p.G), hq_e = (uint32_t)(hkv * p.G + r_row % p.G), hg_e = (uint32_t)lane_e >> 5;
-        const float inv = 1.f / ltot;
-        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq_e * p.s_o.head + (int64_t)qi_e * p.s_o.token;
+        const int r_row = rt * BM + wave * 32 + (lane_e & 31);
+        if (r_row / p.G < p.tq) {
+            const uint32_t qi_e = (uint32_t)(r_row / p.G), hq_e = (uint32_t)(hkv * p.G + r_row % p.G), hg_e = (uint32_t)lane_e >> 5;
+            const float inv = 1.f / ltot;
+            bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq_e * p.s_o.head + (int64_t)qi_e * p.s_o.token;
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int j4 = 0; j4 < 4; ++j4) {
-                u32x2 w;
-                w[0] = pack_bf16x2(o[b][db][4 * j4] * inv, o[b][db][4 * j4 + 1] * inv);
-                w[1] = pack_bf16x2(o[b][db][4 * j4 + 2] * inv, o[b][db][4 * j4 + 3] * inv);
-                *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg_e) = w;
-            }
-        if (p.lse && hg_e == 0)
-            p.lse[((int64_t)l * p.Hkv * p.G + hq_e) * p.tq + qi_e] = m[b] * p.scale + logf(ltot);
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    u32x2 w;
+                    w[0] = pack_bf16x2(o[db][4 * j4] * inv, o[db][4 * j4 + 1] * inv);
+                    w[1] = pack_bf16x2(o[db][4 * j4 + 2] * inv, o[db][4 * j4 + 3] * inv);
+                    *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg_e) = w;
+                }
+            if (p.lse && hg_e == 0)
+                p.lse[((int64_t)l * p.Hkv * p.G + hq_e) * p.tq + qi_e] = m * p.scale + logf(ltot);
+        }
     }
 }
 
@@ -676,15 +638,14 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
         if (cache_k.stride_token >= max_tok || cache_v.stride_token >= max_tok) return KVCOMM_EUNSUPPORTED;
     }
     constexpr int NW = KVC_ATTN_NW;    // wavefronts per block
-    constexpr int QB = KVC_ATTN_QB;    // 32-query blocks per wavefront
     constexpr int WPE = KVC_ATTN_WPE;  // wavefronts per SIMD the register budget is sized for
-    const int bm = D == 256 ? 128 : 32 * NW * QB;
+    const int bm = D == 256 ? 128 : 32 * NW;
     p.n_row_tiles = (p.G * tq + bm - 1) / bm;
     const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
     switch (D) {
-        case 64: return launch(attn_mfma_kernel<64, NW, QB, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
-        case 128: return launch(attn_mfma_kernel<128, NW, QB, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
-        case 256: return launch(attn_mfma_kernel<256, 4, 1, 1>, dim3(n_blocks), dim3(256), 0, s, p);
+        case 64: return launch(attn_mfma_kernel<64, NW, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 128: return launch(attn_mfma_kernel<128, NW, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 256: return launch(attn_mfma_kernel<256, 4, 1>, dim3(n_blocks), dim3(256), 0, s, p);
         default: return KVCOMM_EUNSUPPORTED;
     }
 }
