@@ -302,24 +302,36 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     f32x16 sbuf[2];   // scores of sub-step u live in sbuf[u & 1]
     u32x4 pbuf[2][2]; // packed bf16 probabilities of sub-step u live in pbuf[u & 1]
 
-    // Exponentials of elements [16c/NC, 16(c+1)/NC) of s against the reference -> packed bf16 B operands; the row sum
-    // is taken from the ROUNDED values (v_dot2_f32_bf16 with ones) so that numerator and denominator agree.
+    // P = exp2(s * scale * log2(e) - mc) for the 16 scores of this lane, as packed bf16 B operands, and their sum.
+    // The work is cut into the 2 * NKS MFMA slots of a pipeline step and staggered so that no instruction reads
+    // what its own slot produced: element j is scaled in slot b-2, exponentiated in slot b-1 and
+    // summed / packed in slot b = j * NS / 16 (slots -2 and -1 precede the first MFMA).  A wavefront issues in
+    // order, so a dependent chain inside one slot would hold back the next MFMA for its whole latency.
     // Lane (n, hg) holds key rows 8*(j/4) + 4*hg + j%4 of the sub-step; `limit` is its last visible key.
-    auto exp_chunk = [&](const f32x16 &s, u32x4 (&pk)[2], float &rs, float &e_even, int limit, bool masked, int c, int NC)
-                         __attribute__((always_inline)) {
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    // Row sums are plain fp32 additions of the unrounded exponentials (two chains): v_dot2 on the rounded pairs
+    // would agree with the numerator to the last bit, but it shares a pipeline with the MFMAs and costs four
+    // times as much next to them; the difference is a relative 2^-9 / sqrt(keys) of the denominator.
+    struct ExpState {
+        float x[16], e[16], rs_even, rs_odd;
+    };
+    auto exp_slot = [&](const f32x16 &s, u32x4 (&pk)[2], ExpState &st, int limit, bool masked, int t, int NS)
+                        __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            if (j * NC / 16 != c) continue;
-            float v = s[j];
-            if (masked) v = 8 * (j >> 2) + 4 * hg + (j & 3) > limit ? -INFINITY : v;
-            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(v, p.scale_log2, -mc));
-            if (j & 1) {
-                const uint32_t pr = pack_bf16x2(e_even, e);
-                pk[j >> 3][(j & 7) >> 1] = pr;
-                rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pr), ones, rs, false);
-            } else {
-                e_even = e;
+            const int b = j * NS / 16;
+            if (b - 2 == t) {
+                float v = s[j];
+                if (masked) v = 8 * (j >> 2) + 4 * hg + (j & 3) > limit ? -INFINITY : v;
+                st.x[j] = __builtin_fmaf(v, p.scale_log2, -mc);
+            }
+            if (b - 1 == t) st.e[j] = __builtin_amdgcn_exp2f(st.x[j]);
+            if (b == t) {
+                if (j & 1) {
+                    pk[j >> 3][(j & 7) >> 1] = pack_bf16x2(st.e[j - 1], st.e[j]);
+                    st.rs_odd += st.e[j];
+                } else {
+                    st.rs_even += st.e[j];
+                }
             }
         }
     };
@@ -346,10 +358,11 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int j = 0; j < 16; ++j) o[db][j] *= corr;
-        float rs = 0.f, e_even = 0.f;
+        ExpState st;
+        st.rs_even = st.rs_odd = 0.f;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) exp_chunk(s, pk, rs, e_even, limit, masked, c, 4);
-        return rs;
+        for (int t = -2; t < 16; ++t) exp_slot(s, pk, st, limit, masked, t, 16);
+        return st.rs_even + st.rs_odd;
     };
     constexpr float kOverflow = 1073741824.f;  // 2^30
 
@@ -375,7 +388,12 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         }
         va[0] = read_v(vl, 0);
         va[1] = read_v(vl, 1);
-        float rs = 0.f, e_even = 0.f;
+        ExpState st;
+        st.rs_even = st.rs_odd = 0.f;
+        if (DO_EXP) {
+            exp_slot(s_exp, pbuf[(U4 + 1) & 1], st, limit, MASKED, -2, 2 * NKS);
+            exp_slot(s_exp, pbuf[(U4 + 1) & 1], st, limit, MASKED, -1, 2 * NKS);
+        }
 #pragma unroll
         for (int i = 0; i < NKS; ++i) {
             if (DO_QK) {
@@ -389,14 +407,15 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
                 }
                 if (i + 2 < NKS) ka[i + 2] = read_k(kl, i + 2);
             }
-            if (DO_EXP) exp_chunk(s_exp, pbuf[(U4 + 1) & 1], rs, e_even, limit, MASKED, 2 * i, 2 * NKS);
+            if (DO_EXP) exp_slot(s_exp, pbuf[(U4 + 1) & 1], st, limit, MASKED, 2 * i, 2 * NKS);
             __builtin_amdgcn_sched_barrier(0);
             o[i % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], pf[i / NDB], o[i % NDB], 0, 0, 0);
             if (i + 2 < NKS) va[i + 2] = read_v(vl, i + 2);
-            if (DO_EXP) exp_chunk(s_exp, pbuf[(U4 + 1) & 1], rs, e_even, limit, MASKED, 2 * i + 1, 2 * NKS);
+            if (DO_EXP) exp_slot(s_exp, pbuf[(U4 + 1) & 1], st, limit, MASKED, 2 * i + 1, 2 * NKS);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (DO_EXP) {
+            float rs = st.rs_even + st.rs_odd;
             if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(rs < kOverflow)) != 0, 0)) rs = rereference(s_exp, pbuf[(U4 + 1) & 1], limit, MASKED);
             lsum += rs;
         }
