@@ -327,7 +327,9 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             if (b - 1 == t) st.e[j] = __builtin_amdgcn_exp2f(st.x[j]);
             if (b == t) {
                 if (j & 1) {
-                    pk[j >> 3][(j & 7) >> 1] = pack_bf16x2(st.e[j - 1], st.e[j]);
+                    uint32_t pr = pack_bf16x2(st.e[j - 1], st.e[j]);
+                    asm volatile("" : "+v"(pr));  // keeps the conversion in this slot (it would sink to its use, a step later)
+                    pk[j >> 3][(j & 7) >> 1] = pr;
                     st.rs_odd += st.e[j];
                 } else {
                     st.rs_even += st.e[j];
