@@ -159,18 +159,6 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     const bf16_t *kb_ = static_cast<const bf16_t *>(p.k) + l * p.s_k.layer + hkv * p.s_k.head;
     const bf16_t *vb_ = static_cast<const bf16_t *>(p.v) + l * p.s_v.layer + hkv * p.s_v.head;
 
-    // This lane's query column: row r = i * G + g of the (layer, kv head) group.
-    int qi;
-    bf16x8 qf[NKS];
-    {
-        const int r_row = rt * BM + wave * 32 + n;
-        qi = min(r_row / p.G, p.tq - 1);
-        const int hq = hkv * p.G + r_row % p.G;
-        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)(uint32_t)hq * p.s_q.head + (int64_t)(uint32_t)qi * p.s_q.token;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
-    }
-
     // Every wavefront of the block walks the same tiles (one barrier per 64-key tile); the causal
     // mask is applied from the first 32-key sub-step that is partly hidden from some query of the block.
     const int wg_imax = min(p.tq - 1, (rt * BM + BM - 1) / p.G);
@@ -236,6 +224,22 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             load_rows(vbytes, p.s_v.token, v_row_bytes, 64 * tile + wave * RW + it * RPL, ld_voff[it],
                       vbuf + (tile & 1) * TILEB + (wave * RW + it * RPL) * ROWB);
     };
+    // The first tiles are requested before anything else is set up: their latency is the block's start-up time.
+    load_k64(0);    // halves 0, 1
+    load_k64(64);   // halves 2, 3
+    load_v64(0);
+    // This lane's query column: row r = i * G + g of the (layer, kv head) group.
+    int qi;
+    bf16x8 qf[NKS];
+    {
+        const int r_row = rt * BM + wave * 32 + n;
+        qi = min(r_row / p.G, p.tq - 1);
+        const int hq = hkv * p.G + r_row % p.G;
+        const bf16_t *qrow = static_cast<const bf16_t *>(p.q) + l * p.s_q.layer + (int64_t)(uint32_t)hq * p.s_q.head + (int64_t)(uint32_t)qi * p.s_q.token;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = as_bf16x8(load16(qrow + ks * 16 + hg * 8));
+    }
+
     // Steady state (all rows exist, no half is skipped): the same loads from two running row pointers,
     // so that a load costs one 64-bit scalar add instead of a 64-bit multiply, and with M0 formed from
     // a per-wavefront LDS base plus a literal.  kp / vp point at this wavefront's next row to load:
@@ -433,9 +437,6 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     // ---- pipeline over tiles.  During tile t the sub-steps 2t and 2t+1 read K halves 2t+2 and 2t+3 and V tile t;
     // the loads issued at its start (K halves 2t+4, 2t+5 into the slots of halves 2t and 2t+1, V tile t+1 into the
     // buffer of tile t-1) only overwrite what tile t-1 finished reading.
-    load_k64(0);    // halves 0, 1
-    load_k64(64);   // halves 2, 3
-    load_v64(0);
     tile_barrier();
 
     // Prologue: S(0) and S(1); the reference of every query from S(0) (key 0 is visible to all); P(0).
