@@ -34,48 +34,176 @@ HBM_TRAFFIC_BYTES = {"align_kv": 2416138240 + 268435456, "anchor_weights": 12081
 
 
 def cpu_baseline(w):
-    """Oracle (as it stands) on a bounded sample: the eight segment alignments (all layers) and the suffix
-    attention of two whole agents; scaled to the whole workload by segment / agent counts."""
+    """Oracle (as it stands) over the WHOLE workload: every segment alignment and the suffix attention of every
+    agent, all layers and heads, one agent's inputs on the host at a time (about half a minute for config 2)."""
     import torch
 
     import oracle
     from paper_2510_12872_amd import workloads
 
     f64 = lambda t: t.to(torch.float64).numpy()
-    n_seg = 2 * w.n_segments                 # every segment of two agents
-    t_align_sample = 0.0
-    for j in range(n_seg):
-        seg = workloads.make_segment(w, j // w.n_segments, j % w.n_segments, "cpu")
-        args = (f64(seg.base_k), f64(seg.base_v), [f64(a) for a in seg.anchor_k],
-                [f64(a) for a in seg.anchor_dk], [f64(a) for a in seg.anchor_dv])
-        t0 = time.perf_counter()
-        oracle.reuse_step(*args, seg.delta_pos, w.rope_theta, tau=w.temperature)
-        t_align_sample += time.perf_counter() - t0
-        del seg, args
-    t_align = t_align_sample * (w.n_segments * w.n_agents / n_seg)
-
-    n_attn = 2                               # every layer and q head of two agents
-    wa = workloads.scaled(w, n_agents=n_attn, n_segments=0, prefix_len=w.n_ctx)
-    t_attn_sample = 0.0
-    for a in range(n_attn):
-        ag = workloads.make_agent(wa, a, "cpu")
+    t_align = t_attn = 0.0
+    for a in range(w.n_agents):
+        for j in range(w.n_segments):
+            seg = workloads.make_segment(w, a, j, "cpu")
+            args = (f64(seg.base_k), f64(seg.base_v), [f64(x) for x in seg.anchor_k],
+                    [f64(x) for x in seg.anchor_dk], [f64(x) for x in seg.anchor_dv])
+            t0 = time.perf_counter()
+            oracle.reuse_step(*args, seg.delta_pos, w.rope_theta, tau=w.temperature)
+            t_align += time.perf_counter() - t0
+            del seg, args
+        # the attention reads a cache of the right shape; its segment slots hold generator values (the oracle's
+        # own aligned rows would cost the same to attend over)
+        ag = workloads.make_agent(workloads.scaled(w, n_segments=0, prefix_len=w.n_ctx), a, "cpu")
         q, k, v = f64(ag.q), f64(ag.cache_k), f64(ag.cache_v)
         t0 = time.perf_counter()
-        oracle.suffix_attn(q, k, v, wa.n_ctx)
-        t_attn_sample += time.perf_counter() - t0
+        oracle.suffix_attn(q, k, v, w.n_ctx)
+        t_attn += time.perf_counter() - t0
         del ag, q, k, v
-    t_attn = t_attn_sample * (w.n_agents / n_attn)
+    try:
+        affinity = len(os.sched_getaffinity(0))
+    except AttributeError:
+        affinity = None
     return {
         "value": w.aligned_tokens / (t_align + t_attn),
         "unit": "tokens/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": (f"{n_seg} of {w.n_agents * w.n_segments} segment alignments, all layers ({t_align_sample:.2f} s) + "
-                   f"suffix attention of {n_attn} of {w.n_agents} agents, all layers ({t_attn_sample:.2f} s), "
-                   f"scaled by segment / agent counts"),
+        "sample": (f"whole workload: {w.n_agents * w.n_segments} segment alignments ({t_align:.2f} s) + suffix attention "
+                   f"of {w.n_agents} agents ({t_attn:.2f} s), all layers and heads"),
+        "nproc": os.cpu_count(),
+        "affinity_cores": affinity,
         "align_tokens_per_s": w.aligned_tokens / t_align,
         "attn_gflops": w.attn_flops() / t_attn / 1e9,
     }
+
+
+def _stats(events):
+    """Mean and median of HIP-event pairs, in ms."""
+    ts = sorted(a.elapsed_time(b) for a, b in events)
+    if not ts:
+        return None, None
+    mid = len(ts) // 2
+    med = ts[mid] if len(ts) % 2 else 0.5 * (ts[mid - 1] + ts[mid])
+    return sum(ts) / len(ts), med
+
+
+def config_steps(torch, kv, dev, names=("pool_scaling_a4", "pool_scaling_a16", "pool_scaling_a32", "pool_scaling_a64",
+                                        "long_context", "llama70b"), steps=4, warmup=2):
+    """Whole steps of the other baseline configurations, in the launch configuration of the timed region: per agent
+    one batched weights call, one batched align call into the agent's cache and the suffix attention.  One agent's
+    inputs are generated and every agent of the step runs on them (an agent's pass streams several GB, far beyond
+    the 256 MB last-level cache, so nothing is reused between passes); config 5's four agents would not fit
+    288 GB otherwise.  Per-call HIP events inside the steps give the kernel rates."""
+    from paper_2510_12872_amd import hotpath, workloads
+
+    res = {}
+    for name in names:
+        w = workloads.WORKLOADS[name]
+        model = hotpath.model_of(w)
+        ag = workloads.make_agent(w, 0, dev)
+        out = torch.empty_like(ag.q) if w.tq else None
+        sc = hotpath.AgentScratch(model, [w.seg_len] * w.n_segments, [w.n_anchors] * w.n_segments, kv.W_TOKEN, dev)
+        wjobs = [dict(seg_base_k=seg.base_k, anchor_base_k=seg.anchor_k, anchor_len=seg.anchor_len,
+                      weights_out=sc.weights[j], nearest_out=sc.nearest[j], selected_out=sc.selected[j])
+                 for j, seg in enumerate(ag.segments)]
+        ajobs = [dict(base_k=seg.base_k, base_v=seg.base_v, anchor_dk=seg.anchor_dk, anchor_dv=seg.anchor_dv,
+                      anchor_len=seg.anchor_len, weights=sc.weights[j], delta_pos=seg.delta_pos,
+                      anchor_delta_pos=seg.anchor_delta_pos,
+                      out_k=ag.cache_k[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len],
+                      out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len])
+                 for j, seg in enumerate(ag.segments)]
+        ev = {"weights": [], "align": [], "attn": []}
+
+        def timed(kind, record, fn):
+            if not record:
+                fn()
+                return
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            ev[kind].append((e0, e1))
+
+        def step(record):
+            for _ in range(w.n_agents):
+                timed("weights", record, lambda: kv.kvcomm_anchor_weights_batch(model, wjobs, w.temperature, kv.W_TOKEN,
+                                                                                 workspace=sc.workspace))
+                timed("align", record, lambda: kv.kvcomm_align_kv_batch(model, ajobs, kv.W_TOKEN))
+                if w.tq:
+                    timed("attn", record, lambda: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=out))
+
+        for _ in range(warmup):
+            step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(True)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        one = workloads.scaled(w, n_agents=1)
+        r = {"ms_per_step": ms, "aligned_tokens_per_step": w.aligned_tokens, "tokens_per_s": w.aligned_tokens / (ms * 1e-3),
+             "shape": f"{w.n_agents} agent(s) x {w.n_segments} segment(s) of {w.seg_len}, A {w.n_anchors}, L {w.n_layers}, "
+                      f"Hq {w.n_q_heads}, n_ctx {w.n_ctx}, tq {w.tq}"}
+        for kind, nbytes, key in (("weights", one.distance_bytes(), "distance"), ("align", one.align_bytes(), "align")):
+            mean, med = _stats(ev[kind])
+            r[key] = {"avg_call_ms": mean, "median_call_ms": med, "GBps": nbytes / mean / 1e6,
+                      "frac_of_hbm_peak": nbytes / mean / 1e6 / HBM_PEAK_GBS}
+        if w.tq:
+            mean, med = _stats(ev["attn"])
+            r["attn"] = {"avg_call_ms": mean, "median_call_ms": med, "tflops": one.attn_flops() / mean / 1e9,
+                         "frac_of_mfma_peak": one.attn_flops() / mean / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        res[name] = r
+        del ag, out, sc, wjobs, ajobs
+        torch.cuda.empty_cache()
+    return res
+
+
+def compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs, steps=5, warmup=2):
+    """The timed region's step with every anchor's deviations stored as E4M3 (one byte per element, scale 2^-10):
+    batched weights, batched compressed update, attention."""
+    scale = 2.0 ** -10
+    qjobs = []
+    for ag, sc in zip(agents, scratches):
+        jobs = []
+        for j, seg in enumerate(ag.segments):
+            jobs.append(dict(base_k=seg.base_k, base_v=seg.base_v,
+                             anchor_dk8=[kv.kvcomm_quantize_deltas(model, a, scale) for a in seg.anchor_dk],
+                             anchor_dv8=[kv.kvcomm_quantize_deltas(model, a, scale) for a in seg.anchor_dv],
+                             scale_k=[scale] * w.n_anchors, scale_v=[scale] * w.n_anchors, anchor_len=seg.anchor_len,
+                             weights=sc.weights[j], delta_pos=seg.delta_pos, anchor_delta_pos=seg.anchor_delta_pos,
+                             out_k=ag.cache_k[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len],
+                             out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len]))
+        qjobs.append(jobs)
+    ev = []
+
+    def step(record):
+        for ai, ag in enumerate(agents):
+            kv.kvcomm_anchor_weights_batch(model, wjobs[ai], w.temperature, kv.W_TOKEN, workspace=scratches[ai].workspace)
+            if record:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            kv.kvcomm_align_kv_q8_batch(model, qjobs[ai], kv.W_TOKEN)
+            if record:
+                e1.record()
+                ev.append((e0, e1))
+            kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=outs[ai])
+
+    for _ in range(warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(True)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    mean, med = _stats(ev)
+    rows = w.n_layers * w.n_kv_heads * w.n_segments * w.seg_len          # per launch: the segments of one agent
+    nbytes = rows * w.head_dim * (4 * 2 + 2 * w.n_anchors)
+    return {"ms_per_step": ms, "tokens_per_s": w.aligned_tokens / (ms * 1e-3),
+            "align_kv_q8_batch": {"avg_call_ms": mean, "median_call_ms": med, "algorithmic_bytes": nbytes,
+                                  "GBps": nbytes / mean / 1e6, "frac_of_hbm_peak": nbytes / mean / 1e6 / HBM_PEAK_GBS},
+            "note": "deviations stored as E4M3 x 2^-10 (lossy); same weights and attention calls as the timed region"}
 
 
 def mfma_calibration(torch, kv, w, model, dev):
@@ -292,6 +420,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-events", action="store_true", help="no per-call HIP events in the timed region")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip what follows the timed region (other configurations, compressed deviations)")
+    ap.add_argument("--configs-only", action="store_true",
+                    help="only run the whole steps of configurations 3, 4 and 5 (profiling runs)")
     ap.add_argument("--no-overlap-info", action="store_true",
                     help="skip the two-stream steps that follow the timed region (profiling runs: every launch of "
                          "the trace then ran alone on the chip)")
@@ -354,6 +486,9 @@ def main():
         return
     if args.per_config:
         print(json.dumps({"per_config": per_config(torch, kv, dev)}))
+        return
+    if args.configs_only:
+        print(json.dumps({"configs": config_steps(torch, kv, dev)}))
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
@@ -457,7 +592,10 @@ def main():
         overlap_ms = (time.perf_counter() - t1) / n_ov * 1e3
 
     def avg_ms(kind):
-        return sum(a.elapsed_time(b) for a, b in ev[kind]) / len(ev[kind]) if ev[kind] else None
+        return _stats(ev[kind])[0]
+
+    def med_ms(kind):
+        return _stats(ev[kind])[1]
 
     seg_w = workloads.scaled(w, n_agents=1)                 # one align / weights launch = the segments of one agent
     agent_w = workloads.scaled(w, n_agents=1)                # one attention launch = one agent
@@ -466,18 +604,18 @@ def main():
     if t_align:
         ach = seg_w.align_bytes() / (t_align * 1e-3) / 1e9
         kernels["align_kv"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_align,
+                               "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_align, "median_launch_ms": med_ms("align"),
                                "bytes_per_launch": seg_w.align_bytes(), "traffic": HBM_TRAFFIC_BYTES["align_kv"]}
     if t_weights:
         ach = seg_w.distance_bytes() / (t_weights * 1e-3) / 1e9
         kernels["anchor_weights"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                     "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_weights,
+                                     "frac": ach / HBM_PEAK_GBS, "avg_launch_ms": t_weights, "median_launch_ms": med_ms("weights"),
                                      "bytes_per_launch": seg_w.distance_bytes(), "traffic": HBM_TRAFFIC_BYTES["anchor_weights"],
                                      "note": "two kernels per call (partial distances + softmax finalize)"}
     if t_attn:
         ach = agent_w.attn_flops() / (t_attn * 1e-3) / 1e12
         kernels["suffix_attn"] = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                  "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn,
+                                  "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn, "median_launch_ms": med_ms("attn"),
                                   "flops_per_launch": agent_w.attn_flops(), "traffic": HBM_TRAFFIC_BYTES["suffix_attn"]}
     # dominant kernel = the one with the largest share of a step
     share = {"align_kv": (t_align or 0) * w.n_agents,
@@ -518,6 +656,13 @@ def main():
     elif overlap_ms is not None:
         result["two_stream_overlap"] = {"ms_per_step": overlap_ms, "tokens_per_s": w.aligned_tokens / (overlap_ms * 1e-3),
                                         "note": "same steps, next agent's alignment beside attention; not used for value"}
+    if not args.no_extras and not args.overlap:
+        # After the timed region, for the record: the same step on compressed deviations, then whole steps of the
+        # other baseline configurations (3: pool scaling, 4: long context, 5: 70B shape).
+        result["compressed_deviations"] = compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs)
+        agents.clear(), outs.clear(), scratches.clear(), wjobs.clear(), ajobs.clear()   # config 5 needs the room
+        torch.cuda.empty_cache()
+        result["configs"] = config_steps(torch, kv, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)

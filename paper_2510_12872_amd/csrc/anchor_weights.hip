@@ -90,6 +90,7 @@ struct DistParams {
     Strides s_anc;
     int32_t H, LH, lh_per_block, n_jobs;
     int32_t fused, rule;   // fused: a row's distances are complete inside its lanes; write the weights here
+    int32_t per_segment;   // one weight set per segment: a block also adds up its rows (partial[chunk][tile][anchor])
     double tau;
     const void *anc[KVCOMM_MAX_ANCHORS];  // selected anchors of all segments
     uint8_t col[KVCOMM_MAX_ANCHORS];      // original index of a selected anchor
@@ -159,13 +160,26 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
         }
     }
     // Fixed-shape butterfly over the LPR lanes of a row (all inside one wavefront).
+    __shared__ double rows[RPB][kAnchorTile];
 #pragma unroll
     for (int j = 0; j < kAnchorTile; ++j) {
         if (j < na) {
             double v = acc[j];
 #pragma unroll
             for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
-            if (valid && lir == 0) jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
+            if (p.per_segment) {
+                if (lir == 0) rows[row][j] = valid ? v : 0.0;
+            } else if (valid && lir == 0) {
+                jb.partial[((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j] = v;
+            }
+        }
+    }
+    if (p.per_segment) {  // the block's rows in a fixed order: one partial per (chunk, token tile, anchor)
+        __syncthreads();
+        if (tid < na) {
+            double v = 0.0;
+            for (int r = 0; r < RPB; ++r) v += rows[r][tid];
+            jb.partial[((int64_t)chunk * jb.n_token_tiles + tile) * jb.n_sel + a0 + tid] = v;
         }
     }
 }
@@ -297,6 +311,7 @@ __global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p)
     const int lh0 = chunk * p.lh_per_block;
     const int lh1 = min(lh0 + p.lh_per_block, p.LH);
 
+    __shared__ double rows[RPB][kCosTile][3];
     double dot[kCosTile], ny[kCosTile], nx = 0.0;
 #pragma unroll
     for (int j = 0; j < kCosTile; ++j) dot[j] = ny[j] = 0.0;
@@ -339,12 +354,27 @@ __global__ __launch_bounds__(kBlock) void cos_partial_kernel(const DistParams p)
                 u += __shfl_xor(u, off, LPR);
                 v += __shfl_xor(v, off, LPR);
             }
-            if (valid && lir == 0) {
+            if (p.per_segment) {
+                if (lir == 0) {
+                    rows[row][j][0] = valid ? u : 0.0;
+                    rows[row][j][1] = valid ? nx : 0.0;
+                    rows[row][j][2] = valid ? v : 0.0;
+                }
+            } else if (valid && lir == 0) {
                 const int64_t i = ((int64_t)chunk * jb.S + t) * jb.n_sel + a0 + j;
                 jb.partial[i] = u;
                 jb.partial[jb.comp_stride + i] = nx;
                 jb.partial[2 * jb.comp_stride + i] = v;
             }
+        }
+    }
+    if (p.per_segment) {
+        __syncthreads();
+        if (tid < 3 * na) {
+            const int j = tid / 3, c = tid % 3;
+            double v = 0.0;
+            for (int r = 0; r < RPB; ++r) v += rows[r][j][c];
+            jb.partial[c * jb.comp_stride + ((int64_t)chunk * jb.n_token_tiles + tile) * jb.n_sel + a0 + j] = v;
         }
     }
 }
@@ -356,7 +386,7 @@ struct FinalJob {
     int32_t *selected_out;
     int64_t comp_stride;   // cosine rule: elements between the three partial components
     uint64_t sel_mask;     // bit a = anchor a is selected
-    int32_t S, n_slots, n_anchors, chunk_lanes, block0;
+    int32_t S, n_slots, n_anchors, chunk_lanes, block0, n_token_tiles;
     int16_t a0, n_sel;     // its selected anchors: entries [a0, a0 + n_sel) of col
 };
 
@@ -464,11 +494,13 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
     if (active && cl == 0) slot_softmax(p, jb, dsh + sl * jb.n_sel, a, slot);
 }
 
-// Per-segment granularity: one block per segment; each selected anchor's partials are added by the 256
-// threads in a fixed strided order and then by a fixed LDS tree.
+// Per-segment granularity: one block per segment.  The distance kernel has left one partial per (chunk, token
+// tile, anchor), n_rows = n_chunks * n_token_tiles rows of n_sel values.  Thread t adds the rows g, g + G, ... of
+// anchor t % n_sel (g = t / n_sel, G = 256 / n_sel groups: consecutive threads read consecutive addresses) and a
+// fixed-order sum over the groups closes each anchor, so the result does not depend on timing.
 __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalParams p)
 {
-    __shared__ double red[kBlock];
+    __shared__ double red[3][kBlock];
     __shared__ double dsh[KVCOMM_MAX_ANCHORS];
     const FinalJob &jb = p.job[blockIdx.x];
     const int tid = threadIdx.x;
@@ -478,26 +510,32 @@ __global__ __launch_bounds__(kBlock) void finalize_segment_kernel(const FinalPar
         if (tid == 0 && jb.nearest) jb.nearest[0] = -1;
         return;
     }
-    const int64_t n = (int64_t)p.n_chunks * jb.S;
+    const int n_sel = jb.n_sel, G = kBlock / n_sel;
+    const int a = tid % n_sel, g = tid / n_sel;
+    const int64_t n_rows = (int64_t)p.n_chunks * jb.n_token_tiles;
     const int n_comp = p.rule == KVCOMM_RULE_COSINE_SOFTMAX ? 3 : 1;
-    for (int a = 0; a < jb.n_sel; ++a) {
-        double tot[3] = {0.0, 0.0, 0.0};
+    double s[3][4] = {};   // four interleaved chains per component keep several loads in flight
+    if (g < G) {
         for (int c = 0; c < n_comp; ++c) {
-            double s = 0.0;
-            for (int64_t i = tid; i < n; i += kBlock) s += jb.partial[c * jb.comp_stride + i * jb.n_sel + a];
-            red[tid] = s;
-            __syncthreads();
-            for (int off = kBlock / 2; off >= 1; off >>= 1) {
-                if (tid < off) red[tid] += red[tid + off];
-                __syncthreads();
+            const double *src = jb.partial + c * jb.comp_stride + a;
+            int64_t r = g;
+            for (; r + 3 * G < n_rows; r += 4 * G) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) s[c][u] += src[(r + u * G) * n_sel];
             }
-            tot[c] = red[0];
-            __syncthreads();
+            for (int u = 0; r < n_rows; r += G, ++u) s[c][u] += src[r * n_sel];
         }
-        if (tid == 0) dsh[a] = score_of(p, tot[0], tot[1], tot[2]);
+    }
+    for (int c = 0; c < n_comp; ++c) red[c][tid] = (s[c][0] + s[c][1]) + (s[c][2] + s[c][3]);
+    __syncthreads();
+    if (tid < n_sel) {
+        double tot[3] = {0.0, 0.0, 0.0};
+        for (int c = 0; c < n_comp; ++c)
+            for (int gg = 0; gg < G; ++gg) tot[c] += red[c][gg * n_sel + tid];
+        dsh[tid] = score_of(p, tot[0], tot[1], tot[2]);
     }
     __syncthreads();
-    if (tid < jb.n_sel) slot_softmax(p, jb, dsh, tid, 0);
+    if (tid < n_sel) slot_softmax(p, jb, dsh, tid, 0);
 }
 
 template <typename T, int LPR>
@@ -635,6 +673,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
     // (one (layer, head) pair per block, as in the two-stage form: with runs of several pairs per block the
     // softmax of one pair delays the loads of the next, measured 6 % slower)
     dp.fused = fused ? 1 : 0;
+    dp.per_segment = gran == KVCOMM_W_SEGMENT ? 1 : 0;
     dp.rule = rule;
     dp.tau = (double)temperature;
     fp.n_chunks = pl.n_chunks;
@@ -668,6 +707,7 @@ extern "C" int kvcomm_anchor_weights_batch(const kvcomm_model *model, int32_t gr
         fj.nearest = jd.nearest_out;
         fj.selected_out = jd.selected_out;
         fj.comp_stride = dj.comp_stride;
+        fj.n_token_tiles = dj.n_token_tiles;
         fj.S = jd.seg_len;
         fj.n_slots = (int32_t)kvcomm_weight_slots(model, jd.seg_len, gran);
         fj.n_anchors = jd.n_anchors;
