@@ -19,7 +19,15 @@ using namespace kvc;
 #define KVC_ALIGNQ8_BLOCKS 2048   // blocks per tensor and segment the grid of the compressed update aims at
 #endif
 
+#ifndef KVC_ALIGNQ8_WPE
+#define KVC_ALIGNQ8_WPE 4   // wavefronts per SIMD the register budget is sized for
+#endif
+#ifndef KVC_ALIGNQ8_INFLIGHT
+#define KVC_ALIGNQ8_INFLIGHT 2   // anchors loaded together (twice that in flight: two stages); 4 spills at this budget
+#endif
+
 constexpr int kBlock = kAlignBlock;
+constexpr int kQ8InFlight = KVC_ALIGNQ8_INFLIGHT;
 
 // EPV consecutive E4M3 bytes -> floats.
 template <int EPV>
@@ -36,44 +44,50 @@ __device__ __forceinline__ void unpack_q8(const uint32_t (&raw)[EPV / 4], float 
     }
 }
 
-// Deviation bytes of one anchor for this lane's channels of both halves, bf16 rows (8 channels per lane and
-// half = 8 bytes each).  Instead of two 8-byte loads per lane, the two lanes of a pair load 16 bytes each --
-// the even lane the pair's 16 channels of the first half, the odd lane those of the second half -- and
-// swap the halves they do not own with one DPP move per register (quad permutation 1,0,3,2): half as many
-// load instructions for the same bytes.  `row` points at the anchor's row, `pair_off` = 8 * (lane_in_row & ~1).
-struct Q8Pair {
-    u32x4 raw;   // as loaded
-};
-__device__ __forceinline__ Q8Pair load_q8_pair(const uint8_t *row, int pair_off, bool odd, int half_bytes)
-{
-    Q8Pair r;
-    r.raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + pair_off + (odd ? half_bytes : 0)));
-    return r;
-}
-__device__ __forceinline__ void split_q8_pair(const Q8Pair &r, bool odd, uint32_t (&lo)[2], uint32_t (&hi)[2])
-{
-    // even lane holds [lo_even, lo_odd], odd lane holds [hi_even, hi_odd] (8 bytes each)
-    const uint32_t s0 = odd ? r.raw[0] : r.raw[2];   // what the partner needs: even sends lo_odd, odd sends hi_even
-    const uint32_t s1 = odd ? r.raw[1] : r.raw[3];
-    const uint32_t g0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s0, 0xB1, 0xf, 0xf, true);
-    const uint32_t g1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s1, 0xB1, 0xf, 0xf, true);
-    lo[0] = odd ? g0 : r.raw[0];
-    lo[1] = odd ? g1 : r.raw[1];
-    hi[0] = odd ? r.raw[2] : g0;
-    hi[1] = odd ? r.raw[3] : g1;
-}
-
+// Deviation bytes of one anchor for this lane's channels of both halves.
+// 16-bit rows (8 channels per lane and half = 8 bytes each): instead of two 8-byte loads per lane, the two
+// lanes of a pair load 16 bytes each -- the even lane the pair's 16 channels of the first half, the odd lane
+// those of the second half -- and swap the halves they do not own with one DPP move per register (quad
+// permutation 1,0,3,2): half as many load instructions for the same bytes.
+// fp32 rows (4 channels per lane and half): two 4-byte loads.
+// `row` points at the anchor's bytes of this token, `lir` is the lane's index in the row.
 template <int EPV>
-__device__ __forceinline__ void load_q8(const uint8_t *p, uint32_t (&raw)[EPV / 4])
-{
-    if constexpr (EPV == 8) {
-        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
-        raw[0] = v[0];
-        raw[1] = v[1];
-    } else {
-        raw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+struct Q8Raw;
+template <>
+struct Q8Raw<8> {
+    u32x4 raw;
+    __device__ __forceinline__ void load(const uint8_t *row, int lir, int half_bytes)
+    {
+        raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + 8 * (lir & ~1) + ((lir & 1) ? half_bytes : 0)));
     }
-}
+    __device__ __forceinline__ void split(int lir, uint32_t (&lo)[2], uint32_t (&hi)[2]) const
+    {
+        // even lane holds [lo_even, lo_odd], odd lane holds [hi_even, hi_odd] (8 bytes each)
+        const bool odd = lir & 1;
+        const uint32_t s0 = odd ? raw[0] : raw[2];   // what the partner needs: even sends lo_odd, odd sends hi_even
+        const uint32_t s1 = odd ? raw[1] : raw[3];
+        const uint32_t g0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s0, 0xB1, 0xf, 0xf, true);
+        const uint32_t g1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s1, 0xB1, 0xf, 0xf, true);
+        lo[0] = odd ? g0 : raw[0];
+        lo[1] = odd ? g1 : raw[1];
+        hi[0] = odd ? raw[2] : g0;
+        hi[1] = odd ? raw[3] : g1;
+    }
+};
+template <>
+struct Q8Raw<4> {
+    uint32_t raw[2];
+    __device__ __forceinline__ void load(const uint8_t *row, int lir, int half_bytes)
+    {
+        raw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(row + 4 * lir));
+        raw[1] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(row + 4 * lir + half_bytes));
+    }
+    __device__ __forceinline__ void split(int, uint32_t (&lo)[1], uint32_t (&hi)[1]) const
+    {
+        lo[0] = raw[0];
+        hi[0] = raw[1];
+    }
+};
 
 // ------------------------------------------------------------------------------ quantise
 struct QuantParams {
@@ -84,44 +98,59 @@ struct QuantParams {
     float inv_scale;
 };
 
+#ifndef KVC_QUANT_ROWS
+#define KVC_QUANT_ROWS 4   // rows per thread: that many independent 16-byte loads in flight
+#endif
+
 template <typename T, int LPR>  // LPR lanes per row, each EPV elements
 __global__ __launch_bounds__(kBlock) void quantize_kernel(const QuantParams p)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int RPB = kBlock / LPR;
+    constexpr int U = KVC_QUANT_ROWS;
     const int row = threadIdx.x / LPR, lir = threadIdx.x % LPR;
-    const int tile = blockIdx.x % p.n_token_tiles;
+    const int tile = blockIdx.x % p.n_token_tiles;   // a tile is U * RPB consecutive tokens
     const int lh = blockIdx.x / p.n_token_tiles;
-    const int t = tile * RPB + row;
-    if (t >= p.S) return;
     const int l = lh / p.H, h = lh % p.H;
-    const T *xp = static_cast<const T *>(p.in) + l * p.s_in.layer + h * p.s_in.head + t * p.s_in.token + lir * EPV;
-    float x[EPV];
-    unpack<T>(load16_stream(xp), x);
-    uint32_t w[EPV / 4];
+    const T *xb = static_cast<const T *>(p.in) + l * p.s_in.layer + h * p.s_in.head + lir * EPV;
+    uint8_t *yb = p.out + l * p.s_out.layer + h * p.s_out.head + lir * EPV;
+    u32x4 raw[U];
 #pragma unroll
-    for (int i = 0; i < EPV / 4; ++i) {
-        // The clamp (maximum / minimum by number) turns a NaN into a bound, so NaN inputs are patched
-        // afterwards: their code is 0x7f, the format's NaN, whatever the sign.
-        float c[4];
-        uint32_t nan_bytes = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float v = x[4 * i + e] * p.inv_scale;
-            c[e] = fminf(fmaxf(v, -448.f), 448.f);
-            nan_bytes |= v != v ? 0xffu << (8 * e) : 0u;
-        }
-        int packed = 0;
-        packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], packed, false);
-        packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], packed, true);
-        w[i] = ((uint32_t)packed & ~nan_bytes) | (0x7f7f7f7fu & nan_bytes);
+    for (int u = 0; u < U; ++u) {
+        const int t = (tile * U + u) * RPB + row;
+        if (t < p.S) raw[u] = load16_stream(xb + t * p.s_in.token);
     }
-    uint8_t *yp = p.out + l * p.s_out.layer + h * p.s_out.head + t * p.s_out.token + lir * EPV;
-    if constexpr (EPV == 8) {
-        const u32x2 v = {w[0], w[1]};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(yp));
-    } else {
-        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(yp));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int t = (tile * U + u) * RPB + row;
+        if (t >= p.S) continue;
+        float x[EPV];
+        unpack<T>(raw[u], x);
+        uint32_t w[EPV / 4];
+#pragma unroll
+        for (int i = 0; i < EPV / 4; ++i) {
+            // The clamp (maximum / minimum by number) turns a NaN into a bound, so NaN inputs are patched
+            // afterwards: their code is 0x7f, the format's NaN, whatever the sign.
+            float c[4];
+            uint32_t nan_bytes = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = x[4 * i + e] * p.inv_scale;
+                c[e] = fminf(fmaxf(v, -448.f), 448.f);
+                nan_bytes |= v != v ? 0xffu << (8 * e) : 0u;
+            }
+            int packed = 0;
+            packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], packed, false);
+            packed = __builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], packed, true);
+            w[i] = ((uint32_t)packed & ~nan_bytes) | (0x7f7f7f7fu & nan_bytes);
+        }
+        uint8_t *yp = yb + t * p.s_out.token;
+        if constexpr (EPV == 8) {
+            const u32x2 v = {w[0], w[1]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(yp));
+        } else {
+            __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(yp));
+        }
     }
 }
 
@@ -149,7 +178,7 @@ __device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t
 // Work split as in align_kernel: LPR = D / (2 * EPV) lanes per row, lane r owns channels [r*EPV, r*EPV+EPV)
 // of both halves; a block is 256 / LPR tokens of a run of (layer, head) pairs of ONE tensor of one segment.
 template <typename T, int LPR>
-__global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params p)
+__global__ __launch_bounds__(kBlock, KVC_ALIGNQ8_WPE) void align_q8_kernel(const AlignQ8Params p)
 {
     constexpr int EPV = Elem<T>::EPV;
     constexpr int HALF = LPR * EPV;
@@ -204,16 +233,38 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
     const int64_t col0 = (int64_t)lir * EPV;
     auto anchor_row = [&](int a) { return static_cast<const uint8_t *>(p.anc[which][a0 + a]); };
 
-    for (int lh = lh0; lh < lh1; ++lh) {
+    // What one (layer, head) pair needs first: the base row and the first kQ8InFlight anchors.  The loads of
+    // the next pair are issued before the arithmetic of the current one (registers double-buffered).
+    struct Stage {
+        u32x4 rlo, rhi;
+        Q8Raw<EPV> x[kQ8InFlight];
+    };
+    auto anchor_off = [&](int lh) {
+        const int l = lh / p.H, h = lh % p.H;
+        return l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token;
+    };
+    auto issue = [&](int lh, Stage &st) {
         const int l = lh / p.H, h = lh % p.H;
         const T *xp = bp + l * sb.layer + h * sb.head + t * sb.token + col0;
-        const u32x4 rlo = load16_stream(xp), rhi = load16_stream(xp + HALF);
-        const int64_t aoff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token + col0;
+        st.rlo = load16_stream(xp);
+        st.rhi = load16_stream(xp + HALF);
+        const int64_t roff = anchor_off(lh);
+#pragma unroll
+        for (int u = 0; u < kQ8InFlight; ++u)
+            if (u < n_sel) st.x[u].load(anchor_row(u) + roff, lir, HALF);
+    };
+
+    Stage cur;
+    issue(lh0, cur);
+    for (int lh = lh0; lh < lh1; ++lh) {
+        const int l = lh / p.H, h = lh % p.H;
+        Stage nxt;
+        if (lh + 1 < lh1) issue(lh + 1, nxt);
         const float *wrow = p.gran == KVCOMM_W_LAYER_HEAD_TOKEN ? jb.weights + ((int64_t)lh * jb.S + t) * jb.w_pitch : nullptr;
 
         float lo[EPV], hi[EPV];
-        unpack<T>(rlo, lo);
-        unpack<T>(rhi, hi);
+        unpack<T>(cur.rlo, lo);
+        unpack<T>(cur.rhi, hi);
         if (rot_base) {
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
@@ -222,7 +273,9 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
                 hi[e] = b * bc[e] + a * bs[e];
             }
         }
-        auto accumulate = [&](int a, const uint32_t (&rdlo)[EPV / 4], const uint32_t (&rdhi)[EPV / 4]) {
+        auto accumulate = [&](int a, const Q8Raw<EPV> &raw) {
+            uint32_t rdlo[EPV / 4], rdhi[EPV / 4];
+            raw.split(lir, rdlo, rdhi);
             const float w = wrow ? wrow[p.col[a0 + a]] * pow2f(p.scale_exp[which][a0 + a]) : w_lds[row * n_sel + a];
             float dlo[EPV], dhi[EPV];
             unpack_q8<EPV>(rdlo, dlo);
@@ -244,52 +297,28 @@ __global__ __launch_bounds__(kBlock, 4) void align_q8_kernel(const AlignQ8Params
                 hi[e] += w * dhi[e];
             }
         };
-        // four anchors in flight
-        int a = 0;
-        if constexpr (EPV == 8) {
-            // 16-byte loads shared by lane pairs (see load_q8_pair)
-            const bool odd = lir & 1;
-            const int64_t roff = l * p.s_anc.layer + h * p.s_anc.head + t * p.s_anc.token;
-            const int pair_off = 8 * (lir & ~1);
-            for (; a + 4 <= n_sel; a += 4) {
-                Q8Pair x[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) x[u] = load_q8_pair(anchor_row(a + u) + roff, pair_off, odd, HALF);
+        for (int u = 0; u < kQ8InFlight; ++u)
+            if (u < n_sel) accumulate(u, cur.x[u]);
+        // further anchors: kQ8InFlight at a time
+        const int64_t roff = anchor_off(lh);
+        int a = kQ8InFlight;
+        for (; a + kQ8InFlight <= n_sel; a += kQ8InFlight) {
+            Q8Raw<EPV> x[kQ8InFlight];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    uint32_t x0[2], x1[2];
-                    split_q8_pair(x[u], odd, x0, x1);
-                    accumulate(a + u, x0, x1);
-                }
-            }
-            for (; a < n_sel; ++a) {
-                uint32_t x0[2], x1[2];
-                split_q8_pair(load_q8_pair(anchor_row(a) + roff, pair_off, odd, HALF), odd, x0, x1);
-                accumulate(a, x0, x1);
-            }
-        } else {
-            for (; a + 4 <= n_sel; a += 4) {
-                uint32_t x[4][2][EPV / 4];
+            for (int u = 0; u < kQ8InFlight; ++u) x[u].load(anchor_row(a + u) + roff, lir, HALF);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint8_t *d = anchor_row(a + u) + aoff;
-                    load_q8<EPV>(d, x[u][0]);
-                    load_q8<EPV>(d + HALF, x[u][1]);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) accumulate(a + u, x[u][0], x[u][1]);
-            }
-            for (; a < n_sel; ++a) {
-                uint32_t x0[EPV / 4], x1[EPV / 4];
-                const uint8_t *d = anchor_row(a) + aoff;
-                load_q8<EPV>(d, x0);
-                load_q8<EPV>(d + HALF, x1);
-                accumulate(a, x0, x1);
-            }
+            for (int u = 0; u < kQ8InFlight; ++u) accumulate(a + u, x[u]);
+        }
+        for (; a < n_sel; ++a) {
+            Q8Raw<EPV> x;
+            x.load(anchor_row(a) + roff, lir, HALF);
+            accumulate(a, x);
         }
         T *yp = op + l * so.layer + h * so.head + t * so.token + col0;
         store16_stream(yp, pack<T>(lo));
         store16_stream(yp + HALF, pack<T>(hi));
+        cur = nxt;   // (indeterminate after the last pair, and unused)
     }
 }
 
@@ -341,7 +370,7 @@ extern "C" int kvcomm_quantize_deltas(const kvcomm_model *model, kvcomm_tensor i
     p.LH = model->n_layers * model->n_kv_heads;
     p.inv_scale = 1.f / scale;
     const int lpr = model->head_dim / (16 / elem_size(dt));
-    const int rpb = kBlock / lpr;
+    const int rpb = (kBlock / lpr) * KVC_QUANT_ROWS;   // tokens per block
     p.n_token_tiles = (n_tokens + rpb - 1) / rpb;
     const int64_t n_blocks = (int64_t)p.n_token_tiles * p.LH;
     if (n_blocks > 0x7fffffff) return KVCOMM_EUNSUPPORTED;
