@@ -226,30 +226,87 @@ def test_attention_large_scores_and_custom_scale():
     check_close(to_np(out), want, w.dtype, "O")
 
 
+@pytest.mark.parametrize("n_ctx,tq", [(0, 512), (40, 512), (0, 300)])
+def test_attention_short_context_full_blocks(n_ctx, tq):
+    """Blocks of eight wavefronts whose row tile sees three or more key tiles with next to no context before it.
+
+    The first two 32-key halves of a block are read before the main loop, and the first tile of the loop requests
+    the fifth and sixth halves into the same two slots of the ring of key buffers: a barrier after the first
+    scores keeps a fast wavefront's request from overwriting keys that a slow one has not read yet.  With so
+    short a context every block reaches that reuse at once, on every (layer, head)."""
+    w = scaled(SMALL_BF16, n_layers=3, n_kv_heads=2, n_q_heads=8, prefix_len=n_ctx, n_segments=0, tq=tq)
+    say(f"attn short context n_ctx={n_ctx} tq={tq}")
+    model = hotpath.model_of(w)
+    agent = workloads.make_agent(w, 3, DEV)
+    out = kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx)
+    torch.cuda.synchronize()
+    want = oracle.suffix_attn(to_np(agent.q), to_np(agent.cache_k), to_np(agent.cache_v), w.n_ctx)
+    check_close(to_np(out), want, w.dtype, "O")
+
+
 # ------------------------------------------------- full-size configurations, sampled outputs
-def sample_tokens(S, seed):
+def sample_tokens(S, seed, n_min=64):
+    """At least n_min tokens of a segment: both ends, every multiple of 16 in the first and the last 128 tokens
+    and the middle one with its two neighbours (the kernels' blocks take 16 or 32 tokens, so these are the first
+    and last rows of blocks at the start, in the middle and in the ragged end of the grid), the rest random."""
+    edges = {0, 1, S - 2, S - 1}
+    for m in list(range(16, min(S, 129), 16)) + list(range(max(S - 128, 16), S, 16)) + [S // 2]:
+        edges.update((m - 1, m, m + 1))
+    tokens = {t for t in edges if 0 <= t < S}
     g = np.random.default_rng(seed)
-    return sorted(set([0, 1, S // 2, S - 2, S - 1] + g.integers(0, S, 6).tolist()))
+    while len(tokens) < min(n_min, S):
+        tokens.add(int(g.integers(0, S)))
+    return sorted(tokens)
 
 
-def check_agent_sampled(w, agent_id, seg_ids, n_heads_checked=3, chain=True):
+def attention_pairs(w, seed):
+    """(layer, query head) pairs: every position g of the grouped-query group, on the first and the last kv head
+    in turn, layers spread over the depth; plus the very first and the very last pair."""
+    G = w.n_q_heads // w.n_kv_heads
+    g = np.random.default_rng(1000 + seed)
+    pairs = [(0, 0), (w.n_layers - 1, w.n_q_heads - 1)]
+    for i in range(G):
+        hk = 0 if i % 2 == 0 else w.n_kv_heads - 1
+        pairs.append((int(g.integers(w.n_layers)), hk * G + i))
+    for i in range(G):                                   # the other kv head for each g
+        hk = w.n_kv_heads - 1 if i % 2 == 0 else 0
+        pairs.append((int(g.integers(w.n_layers)), hk * G + i))
+    return sorted(set(pairs))
+
+
+def oracle_token_weights(w, seg, layers_per_chunk=8):
+    """The oracle's per-token weights of ALL tokens of a full-size segment.
+
+    The oracle's distance is the root of a sum of squares over (layer, head, channel).  To stay within host
+    memory it is called on chunks of layers and the squares of its values are added: the root of that sum is
+    its value on all layers (up to the order of the additions)."""
+    L = seg.base_k.shape[0]
+    sq, sel = None, None
+    for l0 in range(0, L, layers_per_chunk):
+        l1 = min(l0 + layers_per_chunk, L)
+        d, sel = oracle.distances(to_np(seg.base_k[l0:l1]), [to_np(a[l0:l1]) for a in seg.anchor_k])
+        sq = d * d if sq is None else sq + d * d
+    return oracle.weights(np.sqrt(sq), sel, w.temperature)
+
+
+def check_agent_sampled(w, agent_id, seg_ids=None, chain=True):
     """Full-size parity of one agent.
 
-    Every segment: weights / nearest / selected / K^ / V^ on sampled tokens (all layers and heads).
+    Every segment in seg_ids (default: all): weights / nearest / selected / K^ / V^ on sampled tokens (all
+    layers and heads).
     chain=True: the oracle also computes the weights of ALL tokens and aligns the sampled kv heads
     itself, so the attention check runs end to end with no oracle input taken from the GPU path.
-    chain=False (anchor pools too large to move to the host in test time): attention is checked on a
-    cache whose segment slots hold generator values, then the aligned cache is checked for sanity.
+    chain=False: attention is checked on a cache whose segment slots hold generator values, then the
+    aligned cache is checked for sanity.
     """
     model = hotpath.model_of(w)
     G = w.n_q_heads // w.n_kv_heads
+    seg_ids = range(w.n_segments) if seg_ids is None else seg_ids
     agent = workloads.make_agent(w, agent_id, DEV, with_segments=False)
-    g = np.random.default_rng(agent_id)
-    pairs = [(0, 0), (w.n_layers - 1, w.n_q_heads - 1)]
-    pairs += [(int(g.integers(w.n_layers)), int(g.integers(w.n_q_heads))) for _ in range(n_heads_checked - 2)]
+    pairs = attention_pairs(w, agent_id)
     ocache = {}
     if w.tq and not chain:
-        say(f"  {w.name} agent {agent_id} attention on generator-filled cache")
+        say(f"  {w.name} agent {agent_id} attention on generator-filled cache, {len(pairs)} (layer, head) pairs")
         gen = torch.Generator(device=DEV)
         gen.manual_seed(777 + agent_id)
         for c in (agent.cache_k, agent.cache_v):
@@ -262,7 +319,8 @@ def check_agent_sampled(w, agent_id, seg_ids, n_heads_checked=3, chain=True):
     if w.tq and chain:
         for (l, hq) in pairs:
             hk = hq // G
-            ocache[(l, hk)] = (to_np(agent.cache_k[l, hk]), to_np(agent.cache_v[l, hk]))   # generator rows
+            if (l, hk) not in ocache:
+                ocache[(l, hk)] = (to_np(agent.cache_k[l, hk]), to_np(agent.cache_v[l, hk]))   # generator rows
     guard_k = agent.cache_k[:, :, : w.prefix_len].clone()
     for j in range(w.n_segments):
         say(f"  {w.name} agent {agent_id} segment {j}")
@@ -278,8 +336,7 @@ def check_agent_sampled(w, agent_id, seg_ids, n_heads_checked=3, chain=True):
         assert torch.allclose(ws, torch.ones_like(ws), atol=1e-5)
         assert torch.isfinite(ok.float()).all() and torch.isfinite(ov.float()).all()
         if ocache:
-            dist, sel = oracle.distances(to_np(seg.base_k), [to_np(a) for a in seg.anchor_k])
-            wts, nearest = oracle.weights(dist, sel, w.temperature)
+            wts, nearest = oracle_token_weights(w, seg)
             assert np.array_equal(sc.nearest.cpu().numpy(), nearest)
             check_weights(sc.weights.cpu().numpy(), wts.T)
             for (l, hk), (ck, cv) in ocache.items():
@@ -288,6 +345,9 @@ def check_agent_sampled(w, agent_id, seg_ids, n_heads_checked=3, chain=True):
                                       [cut(a) for a in seg.anchor_dv], wts, seg.delta_pos, w.rope_theta,
                                       seg.anchor_delta_pos)
                 ck[p0:p0 + S], cv[p0:p0 + S] = rk[0, 0], rv[0, 0]
+                # every token of these (layer, kv head) rows of the aligned cache, not only the sampled ones
+                check_close(to_np(ok[l, hk]), rk[0, 0], w.dtype, f"K^[{l},{hk}] seg {j}")
+                check_close(to_np(ov[l, hk]), rv[0, 0], w.dtype, f"V^[{l},{hk}] seg {j}")
         del seg
     assert torch.equal(agent.cache_k[:, :, : w.prefix_len], guard_k)
     if not w.tq:
@@ -302,23 +362,47 @@ def check_agent_sampled(w, agent_id, seg_ids, n_heads_checked=3, chain=True):
         check_close(to_np(out[l, hq]), want[0, 0], w.dtype, f"O[{l},{hq}]")
 
 
+def test_sampled_tokens_and_pairs_cover_the_edges():
+    for S in (512, 1024, 2048):
+        t = sample_tokens(S, 0)
+        assert len(t) >= 64 and t[0] == 0 and t[-1] == S - 1
+        assert {15, 16, 17, 31, 32, 33, S - 33, S - 32, S - 31, S - 17, S - 16, S - 15} <= set(t)
+    for w in (workloads.LLAMA8B_5AGENTS, workloads.LONG_CONTEXT, workloads.LLAMA70B):
+        G = w.n_q_heads // w.n_kv_heads
+        pairs = attention_pairs(w, 0)
+        for hk in (0, w.n_kv_heads - 1):
+            assert {hq % G for _, hq in pairs if hq // G == hk} == set(range(G))
+
+
 def test_config2_llama8b_5agents_sampled():
-    w = workloads.LLAMA8B_5AGENTS
-    check_agent_sampled(w, 0, seg_ids=(0, 3))
-    check_agent_sampled(w, 4, seg_ids=(2,), chain=False)
+    check_agent_sampled(workloads.LLAMA8B_5AGENTS, 0)
+
+
+def test_config2_llama8b_5agents_last_agent_sampled():
+    check_agent_sampled(workloads.LLAMA8B_5AGENTS, 4, chain=False)
 
 
 @pytest.mark.parametrize("w", workloads.POOL_SCALING, ids=lambda w: w.name)
 def test_config3_pool_scaling_sampled(w):
-    check_agent_sampled(w, 0, seg_ids=(0,))
+    check_agent_sampled(w, 0)
 
 
 def test_config4_long_context_sampled():
-    check_agent_sampled(workloads.LONG_CONTEXT, 5, seg_ids=(1,))
+    check_agent_sampled(workloads.LONG_CONTEXT, 5)
 
 
-def test_config5_llama70b_sampled():
-    check_agent_sampled(workloads.LLAMA70B, 2, seg_ids=(3,), n_heads_checked=3, chain=False)
+def test_config4_long_context_second_agent_sampled():
+    check_agent_sampled(workloads.LONG_CONTEXT, 0, chain=False)
+
+
+def test_config5_llama70b_sampled_and_chained():
+    """Every segment on sampled tokens, and the attention of the sampled (layer, head) pairs on a cache the
+    oracle aligned itself from its own all-token weights (distances summed over chunks of layers)."""
+    check_agent_sampled(workloads.LLAMA70B, 2)
+
+
+def test_config5_llama70b_second_agent_sampled():
+    check_agent_sampled(workloads.LLAMA70B, 0, chain=False)
 
 
 def test_config2_batched_launch_as_benchmarked():
@@ -332,8 +416,10 @@ def test_config2_batched_launch_as_benchmarked():
     model = hotpath.model_of(w)
     G = w.n_q_heads // w.n_kv_heads
     agent = workloads.make_agent(w, agent_id, DEV)
-    pairs = [(0, 3), (17, 20), (31, 31)]
-    ocache = {(l, hq // G): (to_np(agent.cache_k[l, hq // G]), to_np(agent.cache_v[l, hq // G])) for l, hq in pairs}
+    pairs = attention_pairs(w, agent_id)
+    ocache = {}
+    for l, hq in pairs:
+        ocache.setdefault((l, hq // G), (to_np(agent.cache_k[l, hq // G]), to_np(agent.cache_v[l, hq // G])))
     sc = hotpath.align_agent_batched(w, model, agent)
     out = kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx)
     torch.cuda.synchronize()
