@@ -26,11 +26,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, GB/s
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
-# HBM bytes per launch on this workload (read + written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# HBM bytes per launch on this workload (read, written), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
-# (profiles/bench_llama8b_5agents_hbm_traffic.md).  Not measured live: counters need the profiler.
-HBM_TRAFFIC_BYTES = {"align_kv": 2416138240 + 268435456, "anchor_weights": 1208109056 + 8389632 + 8493056 + 81920,
-                     "suffix_attn": 537579520 + 134217728}
+# (profiles/bench_llama8b_5agents_hbm_traffic.md; tests/test_bench_constants.py holds the two together).
+# Not measured live: counters need the profiler.
+HBM_TRAFFIC_READ_WRITTEN = {"align_kv": (2416128614, 268435456),                           # align_kernel
+                            "anchor_weights": (1208139366 + 8495309, 8389325 + 82022),     # dist_partial_kernel + finalize_kernel
+                            "suffix_attn": (537181798, 136318874)}                         # attn_mfma_kernel
+HBM_TRAFFIC_BYTES = {k: r + w for k, (r, w) in HBM_TRAFFIC_READ_WRITTEN.items()}
+# Share of the kernel's cycles in which a SIMD's matrix pipe is busy (SQ_VALU_MFMA_BUSY_CYCLES per SIMD over
+# GRBM_GUI_ACTIVE per XCD, profiles/suffix_attn_llama8b_5agents_mfma_counters.md); not measured live either.
+SUFFIX_ATTN_MFMA_BUSY_FRAC = 0.582
 
 
 def cpu_baseline(w):
@@ -424,14 +430,16 @@ def main():
                     help="skip what follows the timed region (other configurations, compressed deviations)")
     ap.add_argument("--configs-only", action="store_true",
                     help="only run the whole steps of configurations 3, 4 and 5 (profiling runs)")
+    ap.add_argument("--config-names", default=None,
+                    help="with --configs-only: comma-separated workload names instead of all of configurations 3-5")
     ap.add_argument("--no-overlap-info", action="store_true",
                     help="skip the two-stream steps that follow the timed region (profiling runs: every launch of "
                          "the trace then ran alone on the chip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference reading for HBM byte counters)")
     ap.add_argument("--hbm-calibration", action="store_true",
-                    help="only time torch's device copy and a read-only reduction over 2 GiB (what plain library "
-                         "kernels sustain from HBM on this box)")
+                    help="only run the stand-alone streaming probe: a read-only pass and a 1:1 copy over 4 GiB (what "
+                         "plain kernels sustain from HBM on this box)")
     ap.add_argument("--per-config", action="store_true",
                     help="only time the kernels of every baseline configuration alone (one segment / one agent)")
     ap.add_argument("--overlap", action="store_true",
@@ -446,6 +454,17 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+    if args.hbm_calibration:
+        # a child process of its own, started before this one touches the GPU
+        import subprocess
+        probe = os.path.join(ROOT, "paper_2510_12872_amd", "tools", "hbm_stream_probe")
+        if not os.path.exists(probe):
+            sys.exit("bench.py: the streaming probe is not built (python -m paper_2510_12872_amd.build)")
+        out = subprocess.run([probe], check=True, capture_output=True, text=True).stdout.strip().splitlines()[-1]
+        res = json.loads(out)
+        res["peak_GBps"] = HBM_PEAK_GBS
+        print(json.dumps(res))
+        return
 
     import torch
 
@@ -466,29 +485,12 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4,
                                                "launches": 5}}))
         return
-    if args.hbm_calibration:
-        src = torch.ones(1 << 29, dtype=torch.float32, device=dev)   # 2 GiB: far beyond the 256 MB last-level cache
-        dst = torch.empty_like(src)
-        res = {}
-        for label, fn, nbytes in (("copy_1_to_1", lambda: dst.copy_(src), 2 * src.numel() * 4),
-                                  ("read_only_sum", lambda: torch.sum(src), src.numel() * 4)):
-            for _ in range(5):
-                fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            res[label + "_GBps"] = nbytes / (e0.elapsed_time(e1) / 20) / 1e6
-        print(json.dumps({"hbm_calibration": res, "peak_GBps": HBM_PEAK_GBS}))
-        return
     if args.per_config:
         print(json.dumps({"per_config": per_config(torch, kv, dev)}))
         return
     if args.configs_only:
-        print(json.dumps({"configs": config_steps(torch, kv, dev)}))
+        names = args.config_names.split(",") if args.config_names else None
+        print(json.dumps({"configs": config_steps(torch, kv, dev, names) if names else config_steps(torch, kv, dev)}))
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
@@ -616,7 +618,8 @@ def main():
         ach = agent_w.attn_flops() / (t_attn * 1e-3) / 1e12
         kernels["suffix_attn"] = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                   "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": t_attn, "median_launch_ms": med_ms("attn"),
-                                  "flops_per_launch": agent_w.attn_flops(), "traffic": HBM_TRAFFIC_BYTES["suffix_attn"]}
+                                  "flops_per_launch": agent_w.attn_flops(), "traffic": HBM_TRAFFIC_BYTES["suffix_attn"],
+                                  "mfma_busy_frac_rocprof": SUFFIX_ATTN_MFMA_BUSY_FRAC}
     # dominant kernel = the one with the largest share of a step
     share = {"align_kv": (t_align or 0) * w.n_agents,
              "anchor_weights": (t_weights or 0) * w.n_agents,
