@@ -17,13 +17,17 @@
 //     applied by choosing which global chunk each lane fetches.  K operands are read with
 //     ds_read_b128; V^T operands with ds_read_b64_tr_b16, which transposes on the way out of
 //     LDS, so V is never transposed by the vector ALU.
-//   * Work advances in 32-key sub-steps that are software pipelined inside each wavefront:
-//     while the matrix cores compute S(u+1) the vector ALU exponentiates S(u); while they
-//     accumulate O += V(u) P(u) it masks and reduces the maximum of S(u+1).  Matrix and vector
-//     instructions are interleaved by hand and pinned with scheduling barriers.
-//   * The softmax reference maximum is lazy: it only moves when the true maximum exceeds it by
-//     2^8, so O is rescaled on very few sub-steps; the row sum is taken from the bf16-rounded
-//     probabilities with v_dot2_f32_bf16.
+//   * Work advances in 32-key sub-steps as a three-stage software pipeline inside each wavefront:
+//     in one step the matrix cores compute S(u+2) = K(u+2) Q^T and O += V(u) P(u), their MFMAs
+//     alternating (two independent accumulator chains), while the vector ALU turns S(u+1) into
+//     P(u+1).  The vector work is cut into one piece per MFMA and staggered so that no instruction
+//     reads what its own piece produced; every piece is pinned by a scheduling barrier.
+//   * The softmax reference is not tracked.  It is set from the first sub-step (key 0 is visible to
+//     every query) and a sub-step only checks that the row sum of its exponentials, which is needed
+//     anyway, stayed below 2^30; a row that did not is re-referenced to its true maximum (O and
+//     the running sum rescaled, the exponentials formed again).  Numerator and denominator share
+//     the reference, so the result is that of the usual online softmax.  Row sums are plain fp32
+//     additions of the unrounded exponentials.
 //   * One barrier per 64 keys; K is kept in a ring of four 32-key halves and V in two 64-key
 //     tiles so that loads run 1-2 tiles ahead of their use.
 //   * A block is eight wavefronts (two per SIMD, 256 registers each) = 256 rows of the packed
