@@ -140,7 +140,10 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
 
     // K: ring of four 32-key halves (half h in slot h & 3); V: two 64-key tiles (tile t in buffer t & 1).
     // Rows are [key][D] with XOR-swizzled 16-byte chunks.
-    __shared__ __align__(16) unsigned char smem[4 * HALFB + 2 * TILEB];
+    // After the last tile the same memory stages the output rows (32 rows per wavefront) for coalesced stores;
+    // the table of row pointers sits behind it.
+    __shared__ __align__(16) unsigned char smem[4 * HALFB + 2 * TILEB + NW * 32 * 8];
+    static_assert(NW * 32 * ROWB <= 4 * HALFB + 2 * TILEB, "output staging must fit the K / V buffers");
     lds_byte *kring = (lds_byte *)smem;
     lds_byte *vbuf = kring + 4 * HALFB;
 
@@ -505,7 +508,11 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         step(2 * t + 1, u1, F_{}, F_{}, T_{});
     }
 
-    // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4
+    // ---- epilogue: normalise and store; lane (n, hg) holds channels 32*db + 8*(j/4) + 4*hg + j%4 of query row n.
+    // Stored straight from these registers a store instruction would scatter 16-byte pieces over 32 rows (8 K
+    // partial-line writes per block, several microseconds of back-pressure).  Instead each wavefront passes its
+    // 32 rows through LDS (8-byte slots XOR-swizzled with the row number so that neither side conflicts much) and
+    // writes them out as whole rows, 16 bytes per lane.
     {
         float ltot;
         {
@@ -515,22 +522,47 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
         // Row coordinates again, from a freshly read lane id: the compiler then keeps none of the
         // prologue's address terms alive across the tile loops.
         const int lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-        const int r_row = rt * BM + wave * 32 + (lane_e & 31);
-        if (r_row / p.G < p.tq) {
-            const uint32_t qi_e = (uint32_t)(r_row / p.G), hq_e = (uint32_t)(hkv * p.G + r_row % p.G), hg_e = (uint32_t)lane_e >> 5;
-            const float inv = 1.f / ltot;
-            bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq_e * p.s_o.head + (int64_t)qi_e * p.s_o.token;
+        const int n_e = lane_e & 31, hg_e = lane_e >> 5;
+        const int r_row = rt * BM + wave * 32 + n_e;
+        const bool valid = r_row / p.G < p.tq;
+        const uint32_t qi_e = (uint32_t)(r_row / p.G), hq_e = (uint32_t)(hkv * p.G + r_row % p.G);
+        bf16_t *orow = static_cast<bf16_t *>(p.out) + l * p.s_o.layer + (int64_t)hq_e * p.s_o.head + (int64_t)qi_e * p.s_o.token;
+        constexpr int SLOTS = 2 * KCH;                       // 8-byte slots per row
+        constexpr int FM = (SLOTS < 32 ? SLOTS : 32) - 1;    // swizzle mask
+        __syncthreads();  // every wavefront has finished reading K and V (and no direct load is outstanding)
+        unsigned char *stage = smem + wave * (32 * ROWB);
+        uint64_t *ptab = reinterpret_cast<uint64_t *>(smem + 4 * HALFB + 2 * TILEB) + wave * 32;
+        if (hg_e == 0) ptab[n_e] = valid ? (uint64_t)(uintptr_t)orow : 0;
+        const float inv = 1.f / ltot;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int j4 = 0; j4 < 4; ++j4) {
-                    u32x2 w;
-                    w[0] = pack_bf16x2(o[db][4 * j4] * inv, o[db][4 * j4 + 1] * inv);
-                    w[1] = pack_bf16x2(o[db][4 * j4 + 2] * inv, o[db][4 * j4 + 3] * inv);
-                    *reinterpret_cast<u32x2 *>(orow + db * 32 + 8 * j4 + 4 * hg_e) = w;
-                }
-            if (p.lse && hg_e == 0)
-                p.lse[((int64_t)l * p.Hkv * p.G + hq_e) * p.tq + qi_e] = m * p.scale + logf(ltot);
+            for (int j4 = 0; j4 < 4; ++j4) {
+                u32x2 w;
+                w[0] = pack_bf16x2(o[db][4 * j4] * inv, o[db][4 * j4 + 1] * inv);
+                w[1] = pack_bf16x2(o[db][4 * j4 + 2] * inv, o[db][4 * j4 + 3] * inv);
+                const int slot = (8 * db + 2 * j4 + hg_e) ^ (n_e & FM);
+                *reinterpret_cast<u32x2 *>(stage + n_e * ROWB + slot * 8) = w;
+            }
+        if (p.lse && hg_e == 0 && valid)
+            p.lse[((int64_t)l * p.Hkv * p.G + hq_e) * p.tq + qi_e] = m * p.scale + logf(ltot);
+        // the reads below touch what other lanes of this wavefront wrote: LDS operations of a wavefront complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int RPS = 64 / KCH;   // rows per store instruction
+        const int c = lane_e % KCH;
+#pragma unroll
+        for (int it = 0; it < 32 / RPS; ++it) {
+            const int row = it * RPS + lane_e / KCH;
+            const int f = row & FM;
+            const u32x2 lo = *reinterpret_cast<const u32x2 *>(stage + row * ROWB + ((2 * c) ^ f) * 8);
+            const u32x2 hi = *reinterpret_cast<const u32x2 *>(stage + row * ROWB + ((2 * c + 1) ^ f) * 8);
+            bf16_t *dst = reinterpret_cast<bf16_t *>((uintptr_t)ptab[row]);
+            if (dst) {
+                const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+                *reinterpret_cast<u32x4 *>(dst + c * 8) = v;
+            }
         }
     }
 }
