@@ -184,6 +184,44 @@ __global__ __launch_bounds__(kBlock) void dist_partial_kernel(const DistParams p
     }
 }
 
+// Reduce-scatter of kAnchorTile per-lane sums over the LPR lanes of a row (LPR a power of two, lanes of a row are
+// consecutive): afterwards lane `lir` holds the row's totals of its own anchors in acc[0 .. max(1, kAnchorTile /
+// LPR)), anchor_of_lane() says which.  Lanes 16 and up of a wider row hold copies that anchor_of_lane() maps
+// past the tile, so they are ignored.
+template <int LPR>
+__device__ __forceinline__ int anchor_of_lane(int lir, int k)
+{
+    if constexpr (LPR >= kAnchorTile)
+        return lir + k * LPR;                       // k == 0: anchor lir (invalid from kAnchorTile on)
+    else
+        return (kAnchorTile / LPR) * lir + k;
+}
+template <int CNT, int OFF, int LPR>
+__device__ __forceinline__ void reduce_scatter_round(double (&acc)[kAnchorTile], int lir)
+{
+    if constexpr (OFF >= 1 && CNT >= 2) {
+        const bool up = lir & OFF;
+#pragma unroll
+        for (int i = 0; i < CNT / 2; ++i) {
+            const double keep = up ? acc[i + CNT / 2] : acc[i];
+            const double send = up ? acc[i] : acc[i + CNT / 2];
+            acc[i] = keep + __shfl_xor(send, OFF, LPR);
+        }
+        reduce_scatter_round<CNT / 2, OFF / 2, LPR>(acc, lir);
+    }
+}
+template <int LPR>
+__device__ __forceinline__ void row_reduce_scatter(double (&acc)[kAnchorTile], int lir)
+{
+    static_assert(kAnchorTile == 16, "written for tiles of 16 anchors");
+#pragma unroll
+    for (int off = LPR / 2; off >= kAnchorTile; off >>= 1)
+#pragma unroll
+        for (int j = 0; j < kAnchorTile; ++j) acc[j] += __shfl_xor(acc[j], off, LPR);
+    constexpr int OFF0 = (LPR < kAnchorTile ? LPR : kAnchorTile) / 2;
+    reduce_scatter_round<kAnchorTile, OFF0, LPR>(acc, lir);
+}
+
 // One softmax per (layer, head, token), pools of up to kAnchorTile selected anchors: a row's distances are
 // complete inside the LPR lanes that read the row, so this kernel finishes the softmax itself and writes the
 // weights (no partial sums, no second kernel).
@@ -229,25 +267,17 @@ __global__ __launch_bounds__(kBlock) void dist_row_softmax_kernel(const DistPara
             for (int j = 0; j < kAnchorTile; ++j)
                 if (j < na) sqdiff_acc<T>(acc[j], x, ra[j]);
         }
-#pragma unroll
-        for (int j = 0; j < kAnchorTile; ++j) {
-            if (j < na) {
-                double v = acc[j];
-#pragma unroll
-                for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, LPR);
-                acc[j] = v;  // every lane of the row now holds the row's sum
-            }
-        }
+        // Sum over the lanes of the row and hand each lane its own anchors in one go: in every round a lane keeps
+        // one half of its values and adds the partner's copy of that half (15 exchanges for 16 anchors over 16
+        // lanes instead of 64 for a butterfly per anchor).  Rows wider than 16 lanes first fold their upper lanes in.
+        row_reduce_scatter<LPR>(acc, lir);
         double sc[NPL];
         double smax = -INFINITY;
         int best = kAnchorTile;
 #pragma unroll
         for (int k = 0; k < NPL; ++k) {
-            const int a = lir + k * LPR;
-            double v = 0.0;
-#pragma unroll
-            for (int j = 0; j < kAnchorTile; ++j) v = j == a ? acc[j] : v;
-            sc[k] = a < na ? -sqrt(v) : -INFINITY;
+            const int a = anchor_of_lane<LPR>(lir, k);
+            sc[k] = a < na ? -sqrt(acc[k]) : -INFINITY;
             if (sc[k] > smax) {  // ascending a: the lowest index wins among equals
                 smax = sc[k];
                 best = a;
@@ -265,7 +295,7 @@ __global__ __launch_bounds__(kBlock) void dist_row_softmax_kernel(const DistPara
         float e[NPL], denom = 0.f;
 #pragma unroll
         for (int k = 0; k < NPL; ++k) {
-            const int a = lir + k * LPR;
+            const int a = anchor_of_lane<LPR>(lir, k);
             e[k] = a < na ? (p.rule == KVCOMM_RULE_NEAREST ? (a == best ? 1.f : 0.f)
                                                            : expf((float)((sc[k] - smax) / p.tau)))
                           : 0.f;
@@ -278,7 +308,7 @@ __global__ __launch_bounds__(kBlock) void dist_row_softmax_kernel(const DistPara
             float *wrow = jb.weights + slot * jb.n_anchors;
 #pragma unroll
             for (int k = 0; k < NPL; ++k) {
-                const int a = lir + k * LPR;
+                const int a = anchor_of_lane<LPR>(lir, k);
                 if (a < na) wrow[p.col[jb.a0 + a]] = e[k] / denom;
             }
             for (int c = lir; c < jb.n_anchors; c += LPR)
