@@ -464,12 +464,14 @@ __device__ __forceinline__ void slot_softmax(const FinalParams &p, const FinalJo
     }
 }
 
-// Per-token and per-(layer, head, token) granularity.  A (slot, selected anchor) pair is summed by
-// CL lanes: lane c adds chunks c, c + CL, ... in increasing order and a fixed butterfly joins the
-// lanes, so the result does not depend on timing; the chunk loads of a lane are all in flight at once.
+// Per-token and per-(layer, head, token) granularity.  A (slot, selected anchor) pair is summed by CL threads:
+// thread (c, slot, anchor) adds chunks c, c + CL, ... in increasing order (its loads all in flight at once; anchor,
+// then slot, vary fastest over the threads, so a wavefront reads whole runs of a chunk's row), the CL sums meet in
+// LDS and are added in increasing c, so the result does not depend on timing.
 __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
 {
     __shared__ double dsh[kBlock];
+    __shared__ double red[3][kBlock];
     int ji = 0;
 #pragma unroll
     for (int i = 1; i < KVCOMM_MAX_BATCH; ++i)
@@ -488,9 +490,10 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
     }
     const int CL = jb.chunk_lanes;             // power of two, CL * n_sel <= kBlock
     const int spb = kBlock / (CL * jb.n_sel);  // slots per block
-    const int cl = tid % CL, a = (tid / CL) % jb.n_sel, sl = tid / (CL * jb.n_sel);
+    const int per_lane = spb * jb.n_sel;       // (slot, anchor) pairs of a block
+    const int a = tid % jb.n_sel, sl = (tid / jb.n_sel) % spb, cl = tid / per_lane;
     const int64_t slot = (int64_t)bx * spb + sl;
-    const bool active = sl < spb && slot < jb.n_slots;
+    const bool active = cl < CL && slot < jb.n_slots;
     const bool cosine = p.rule == KVCOMM_RULE_COSINE_SOFTMAX;
     double s0 = 0.0, s1 = 0.0, s2 = 0.0;
     if (active) {
@@ -503,8 +506,8 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
                     s2 += jb.partial[2 * jb.comp_stride + i];
                 }
             }
-        } else if (cl == 0) {
-            const int64_t i = slot * jb.n_sel + a;  // one chunk per (layer, head): slot = chunk * S + t
+        } else {  // one chunk per (layer, head): slot = chunk * S + t, CL == 1
+            const int64_t i = slot * jb.n_sel + a;
             s0 = jb.partial[i];
             if (cosine) {
                 s1 = jb.partial[jb.comp_stride + i];
@@ -512,11 +515,21 @@ __global__ __launch_bounds__(kBlock) void finalize_kernel(const FinalParams p)
             }
         }
     }
-    for (int off = CL / 2; off >= 1; off >>= 1) {  // lanes of a pair are adjacent
-        s0 += __shfl_xor(s0, off);
+    if (CL > 1) {
+        red[0][tid] = s0;
         if (cosine) {
-            s1 += __shfl_xor(s1, off);
-            s2 += __shfl_xor(s2, off);
+            red[1][tid] = s1;
+            red[2][tid] = s2;
+        }
+        __syncthreads();
+        if (active && cl == 0) {
+            for (int c = 1; c < CL; ++c) {
+                s0 += red[0][c * per_lane + tid];
+                if (cosine) {
+                    s1 += red[1][c * per_lane + tid];
+                    s2 += red[2][c * per_lane + tid];
+                }
+            }
         }
     }
     if (active && cl == 0) dsh[sl * jb.n_sel + a] = score_of(p, s0, s1, s2);
