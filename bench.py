@@ -30,13 +30,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
 # runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
 # (profiles/bench_llama8b_5agents_hbm_traffic.md; tests/test_bench_constants.py holds the two together).
 # Not measured live: counters need the profiler.
-HBM_TRAFFIC_READ_WRITTEN = {"align_kv": (2416128614, 268435456),                           # align_kernel
-                            "anchor_weights": (1208137318 + 8495309, 8390144 + 82022),     # dist_partial_kernel + finalize_kernel
+HBM_TRAFFIC_READ_WRITTEN = {"align_kv": (2416128819, 268435456),                           # align_kernel
+                            "anchor_weights": (1208154522 + 8502477, 8389734 + 82022),     # dist_partial_kernel + finalize_kernel
                             "suffix_attn": (537205146, 136314880)}                         # attn_mfma_kernel
 HBM_TRAFFIC_BYTES = {k: r + w for k, (r, w) in HBM_TRAFFIC_READ_WRITTEN.items()}
 # Share of the kernel's cycles in which a SIMD's matrix pipe is busy (SQ_VALU_MFMA_BUSY_CYCLES per SIMD over
 # GRBM_GUI_ACTIVE per XCD, profiles/suffix_attn_llama8b_5agents_mfma_counters.md); not measured live either.
-SUFFIX_ATTN_MFMA_BUSY_FRAC = 0.594
+SUFFIX_ATTN_MFMA_BUSY_FRAC = 0.606
 
 
 def cpu_baseline(w):
