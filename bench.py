@@ -445,6 +445,8 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="two streams: weights + align of agent i+1 run beside the attention of agent i "
                          "(per-kernel figures then come from a sequential pass before the timed region)")
+    ap.add_argument("--attn-blocks", type=int, default=160,
+                    help="two-stream steps: compute units the attention launch is confined to (0 = the plain launch)")
     ap.add_argument("--next-rows", action="store_true",
                     help="only time the entry points beyond the reuse step proper (weighting variants, offset "
                          "capture, anchor prediction, 8-bit deviations) on one segment of the workload")
@@ -542,15 +544,18 @@ def main():
                                                                 out=outs[ai]))
 
     s_align, s_attn = torch.cuda.Stream(), torch.cuda.Stream()
+    attn_done = [None] * len(agents)
 
     def step_overlapped():
         # The memory-bound alignment of the next agent runs beside the matrix-core-bound attention of the
-        # current one; an event per agent orders attention behind its own alignment.
-        cur = torch.cuda.current_stream()
-        s_align.wait_stream(cur)
-        s_attn.wait_stream(cur)
+        # current one.  The attention is launched as at most --attn-blocks persistent blocks (one per CU), so
+        # that the rest of the chip is free for the alignment kernels.  An event per agent orders attention behind
+        # its own alignment, another one the next step's alignment behind this step's attention of the same
+        # agent (it overwrites the cache slots the attention reads); steps are not separated otherwise.
         for ai, ag in enumerate(agents):
             with torch.cuda.stream(s_align):
+                if attn_done[ai] is not None:
+                    s_align.wait_event(attn_done[ai])
                 kv.kvcomm_anchor_weights_batch(model, wjobs[ai], w.temperature, kv.W_TOKEN,
                                                workspace=scratches[ai].workspace)
                 kv.kvcomm_align_kv_batch(model, ajobs[ai], kv.W_TOKEN)
@@ -558,7 +563,20 @@ def main():
                 aligned.record(s_align)
             with torch.cuda.stream(s_attn):
                 s_attn.wait_event(aligned)
-                kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=outs[ai])
+                if args.attn_blocks > 0:
+                    kv.kvcomm_suffix_attn_confined(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, args.attn_blocks,
+                                                   out=outs[ai])
+                else:
+                    kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=outs[ai])
+                attn_done[ai] = torch.cuda.Event()
+                attn_done[ai].record(s_attn)
+
+    def overlapped_steps(n):
+        cur = torch.cuda.current_stream()
+        s_align.wait_stream(cur)
+        s_attn.wait_stream(cur)
+        for _ in range(n):
+            step_overlapped()
         cur.wait_stream(s_align)
         cur.wait_stream(s_attn)
 
@@ -567,14 +585,13 @@ def main():
     if args.overlap:
         for _ in range(5):               # per-kernel durations, one kernel on the chip at a time
             step(not args.no_events)
-        for _ in range(3):
-            step_overlapped()
+        overlapped_steps(3)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        if args.overlap:
-            step_overlapped()
-        else:
+    if args.overlap:
+        overlapped_steps(args.steps)
+    else:
+        for _ in range(args.steps):
             step(not args.no_events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -583,13 +600,11 @@ def main():
     if not args.overlap and not args.no_overlap_info:
         # For information, after the timed region: the same steps with the next agent's alignment beside the
         # attention of the current one (two streams).  `value` and the rooflines above do not use it.
-        n_ov = max(1, min(args.steps, 10))
-        for _ in range(2):
-            step_overlapped()
+        n_ov = max(1, min(args.steps, 30))
+        overlapped_steps(5)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        for _ in range(n_ov):
-            step_overlapped()
+        overlapped_steps(n_ov)
         torch.cuda.synchronize()
         overlap_ms = (time.perf_counter() - t1) / n_ov * 1e3
 
@@ -655,10 +670,14 @@ def main():
         "kernels": kernels,
     }
     if args.overlap:
-        result["overlap"] = "two streams; roofline / kernels from a sequential pass before the timed region"
+        result["overlap"] = (f"two streams, attention confined to {args.attn_blocks} CUs; roofline / kernels from a "
+                             "sequential pass before the timed region")
     elif overlap_ms is not None:
         result["two_stream_overlap"] = {"ms_per_step": overlap_ms, "tokens_per_s": w.aligned_tokens / (overlap_ms * 1e-3),
-                                        "note": "same steps, next agent's alignment beside attention; not used for value"}
+                                        "attn_blocks": args.attn_blocks, "steps": n_ov,
+                                        "note": "same steps on two streams: the next agent's weights + alignment beside the "
+                                                "attention of the current one, the attention confined to attn_blocks CUs "
+                                                "(kvcomm_suffix_attn_confined); not used for value"}
     if not args.no_extras and not args.overlap:
         # After the timed region, for the record: the same step on compressed deviations, then whole steps of the
         # other baseline configurations (3: pool scaling, 4: long context, 5: 70B shape).

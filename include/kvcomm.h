@@ -235,6 +235,22 @@ int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q,
                        kvcomm_tensor out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same attention (workflow step 4), same arguments, results bit-identical to kvcomm_suffix_attn, launched
+ * as at most `max_blocks` thread blocks that each walk a fixed share of the (layer, kv head, query tile) work
+ * items.  A block of the bf16 kernel fills a compute unit, so the launch occupies max_blocks of the GPU's 256
+ * compute units and leaves the others to kernels that run beside it on another stream: the memory-bound
+ * alignment of the next agent next to the matrix-core-bound attention of the current one.  (Under the chip's
+ * power limit the attention loses less than its share of compute units: measured 0.82 ms on 160 of 256 against
+ * 0.66 ms on all of them.)  max_blocks is spread over the 8 XCDs in launch order; values of at least the number
+ * of work items give the plain launch.  f32 tensors ignore max_blocks (their kernel is small-block and never fills
+ * the chip's registers).
+ * Errors: as kvcomm_suffix_attn; KVCOMM_EINVAL for max_blocks < 8 (one block per XCD is the minimum).          */
+int kvcomm_suffix_attn_confined(const kvcomm_model *model, kvcomm_tensor q,
+                                kvcomm_tensor cache_k, kvcomm_tensor cache_v,
+                                int32_t n_ctx, int32_t tq, float softmax_scale,
+                                kvcomm_tensor out, float *lse_out,
+                                int32_t max_blocks, void *stream);
+
 /* --------------------------------------------------------------------------------------
  * Weighting variants of the appendix on the approximation method: the default rule
  * (softmax of the negative l2 distance), "nearest" (all weight on the selected anchor of

@@ -12,6 +12,6 @@ from .binding import (  # noqa: F401
     kvcomm_anchor_weights_batch, kvcomm_anchor_weights_batch_workspace,
     kvcomm_anchor_weights_rule, kvcomm_anchor_weights_rule_workspace, kvcomm_anchor_weights_static,
     kvcomm_anchor_weights_static_capacity, kvcomm_anchor_weights_workspace,
-    kvcomm_capture_offsets, kvcomm_quantize_deltas, kvcomm_suffix_attn, kvcomm_suffix_attn_workspace, kvcomm_weight_slots, library_path,
+    kvcomm_capture_offsets, kvcomm_quantize_deltas, kvcomm_suffix_attn, kvcomm_suffix_attn_confined, kvcomm_suffix_attn_workspace, kvcomm_weight_slots, library_path,
     load_library,
 )

@@ -122,6 +122,8 @@ def load_library():
     lib.kvcomm_suffix_attn_workspace.restype = sz
     lib.kvcomm_suffix_attn.argtypes = [mp, _CTensor, _CTensor, _CTensor, i32, i32, f32, _CTensor, vp, vp, sz, vp]
     lib.kvcomm_suffix_attn.restype = ctypes.c_int
+    lib.kvcomm_suffix_attn_confined.argtypes = [mp, _CTensor, _CTensor, _CTensor, i32, i32, f32, _CTensor, vp, i32, vp]
+    lib.kvcomm_suffix_attn_confined.restype = ctypes.c_int
     lib.kvcomm_anchor_weights_rule_workspace.argtypes = [mp, i32, i32, i32, i32]
     lib.kvcomm_anchor_weights_rule_workspace.restype = sz
     lib.kvcomm_anchor_weights_rule.argtypes = [mp, i32, i32, f32, _CTensor, i32, ctypes.POINTER(vp), _CTensor,
@@ -295,6 +297,26 @@ def kvcomm_suffix_attn(model, q, cache_k, cache_v, n_ctx, softmax_scale=0.0, out
                                   _desc(cache_k, model.dtype, "cache_k"), _desc(cache_v, model.dtype, "cache_v"),
                                   int(n_ctx), tq, float(softmax_scale), _desc(out, model.dtype, "out"),
                                   None if lse_out is None else lse_out.data_ptr(), None, 0, _stream_ptr(stream)))
+    return (out, lse_out) if want_lse else out
+
+
+def kvcomm_suffix_attn_confined(model, q, cache_k, cache_v, n_ctx, max_blocks, softmax_scale=0.0, out=None,
+                                lse_out=None, want_lse=False, stream=None):
+    """kvcomm_suffix_attn as at most max_blocks persistent thread blocks (one per compute unit)."""
+    lib = load_library()
+    tq = q.shape[2]
+    if cache_k.shape[2] != n_ctx + tq or cache_v.shape[2] != n_ctx + tq:
+        raise KVCommError(-1, "cache_k / cache_v must hold n_ctx + tq tokens")
+    if out is None:
+        out = torch.empty_like(q)
+    if want_lse and lse_out is None:
+        lse_out = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    _check(lib.kvcomm_suffix_attn_confined(ctypes.byref(model.c()), _desc(q, model.dtype, "q"),
+                                           _desc(cache_k, model.dtype, "cache_k"),
+                                           _desc(cache_v, model.dtype, "cache_v"), int(n_ctx), tq,
+                                           float(softmax_scale), _desc(out, model.dtype, "out"),
+                                           None if lse_out is None else lse_out.data_ptr(), int(max_blocks),
+                                           _stream_ptr(stream)))
     return (out, lse_out) if want_lse else out
 
 

@@ -52,6 +52,7 @@ struct AttnParams {
     Strides s_q, s_k, s_v, s_o;
     int32_t L, Hkv, G, n_ctx, tq, N;
     int32_t n_row_tiles;
+    int32_t n_items;   // L * Hkv * n_row_tiles
     float scale;       // softmax scale
     float scale_log2;  // scale * log2(e)
 };
@@ -122,9 +123,23 @@ __device__ __forceinline__ void dma16_sbase_at(const unsigned char *base, uint32
 }
 #pragma clang diagnostic pop
 
-template <int D, int NW, int WPE>
-__global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParams p)
+// PERSIST: the grid is smaller than the number of (layer, kv head, row tile) items and every block walks a
+// fixed share of them (the items of its XCD, strided by the XCD's number of blocks), so that the kernel occupies
+// gridDim.x CUs only and leaves the rest of the chip to whatever runs beside it.  The arithmetic of an item is
+// the same instruction sequence as in the one-item-per-block form.
+template <int D, int NW, int WPE, bool PERSIST>
+__global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParams p_arg)
 {
+    // PERSIST reads the parameters through an opaque pointer to the kernel-argument segment, once per item:
+    // they are then re-loaded (scalar loads) for every item instead of being held in scalar registers for the
+    // whole kernel, which the register budget does not allow.
+    using ParamT = std::conditional_t<PERSIST, const __attribute__((address_space(4))) AttnParams, const AttnParams>;
+    ParamT *p_ptr;
+    if constexpr (PERSIST)
+        p_ptr = (ParamT *)__builtin_amdgcn_kernarg_segment_ptr();
+    else
+        p_ptr = &p_arg;
+    ParamT &p0 = *p_ptr;
     constexpr int NKS = D / 16;      // k-steps of S^T = K Q^T; also the MFMAs of O^T += V^T P^T per sub-step
     constexpr int NDB = D / 32;      // 32-row blocks of O^T
     constexpr int BM = 32 * NW;      // query rows per block (32 per wavefront)
@@ -147,18 +162,29 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
     lds_byte *kring = (lds_byte *)smem;
     lds_byte *vbuf = kring + 4 * HALFB;
 
-    const int tid = threadIdx.x;
+    // XCD-aware item order: hardware deals consecutive block ids round-robin to the 8 XCDs; each XCD gets one
+    // contiguous range of the items (the row tiles of a (layer, kv head) then share its L2).  Block b is the
+    // (b / 8)-th block of XCD b % 8 and takes that range's items b / 8, b / 8 + (blocks of the XCD), ...
+    const int x_id = blockIdx.x & 7;
+    const int x_first = x_id * (p0.n_items >> 3) + min(x_id, p0.n_items & 7);
+    const int x_count = (p0.n_items >> 3) + (x_id < (p0.n_items & 7) ? 1 : 0);
+    const int x_blocks = PERSIST ? ((int)gridDim.x - x_id + 7) >> 3 : x_count;
+    int item = blockIdx.x >> 3;
+    if (PERSIST && item >= x_count) return;   // the whole block: more blocks than items on this XCD
+    do {
+    int logical = x_first + item;
+    int tid = threadIdx.x;
+    ParamT *p_item = p_ptr;
+    if constexpr (PERSIST) {
+        // opaque per item: nothing derived from the item, the thread id or the parameters is kept in registers
+        // across items
+        asm volatile("" : "+s"(logical));
+        asm volatile("" : "+v"(tid));
+        asm volatile("" : "+s"(p_item));
+    }
+    ParamT &p = *p_item;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, n = lane & 31, hg = lane >> 5;
-
-    // XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs;
-    // give each XCD one contiguous range of logical tiles.
-    int logical;
-    {
-        const int nb = gridDim.x, b = blockIdx.x;
-        const int base = nb >> 3, rem = nb & 7, x = b & 7;
-        logical = x * base + min(x, rem) + (b >> 3);
-    }
     const int lh = logical / p.n_row_tiles;
     const int rt = p.n_row_tiles - 1 - logical % p.n_row_tiles;  // longest rows first
     const int l = lh / p.Hkv, hkv = lh % p.Hkv;
@@ -565,6 +591,10 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_mfma_kernel(const AttnParam
             }
         }
     }
+    if (!PERSIST) break;
+    __syncthreads();   // the staging area becomes the K / V buffers of the next item
+    item += x_blocks;
+    } while (item < x_count);
 }
 
 // ------------------------------------------------------------------------------- fp32 path
@@ -644,9 +674,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnParams p)
 
 extern "C" size_t kvcomm_suffix_attn_workspace(const kvcomm_model *, int32_t, int32_t) { return 0; }
 
-extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kvcomm_tensor cache_k,
-                                  kvcomm_tensor cache_v, int32_t n_ctx, int32_t tq, float softmax_scale,
-                                  kvcomm_tensor out, float *lse_out, void *, size_t, void *stream)
+namespace {
+
+// max_blocks > 0: at most that many thread blocks (the bf16 kernel's persistent form when there are more items).
+int suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kvcomm_tensor cache_k, kvcomm_tensor cache_v, int32_t n_ctx,
+                int32_t tq, float softmax_scale, kvcomm_tensor out, float *lse_out, int32_t max_blocks, void *stream)
 {
     int st = check_model(model);
     if (st) return st;
@@ -699,11 +731,38 @@ extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kv
     constexpr int WPE = KVC_ATTN_WPE;  // wavefronts per SIMD the register budget is sized for
     const int bm = D == 256 ? 128 : 32 * NW;
     p.n_row_tiles = (p.G * tq + bm - 1) / bm;
-    const unsigned n_blocks = (unsigned)(p.L * p.Hkv * p.n_row_tiles);
+    p.n_items = p.L * p.Hkv * p.n_row_tiles;
+    if (max_blocks > 0 && max_blocks < p.n_items) {
+        const unsigned n_blocks = (unsigned)max_blocks;
+        switch (D) {
+            case 64: return launch(attn_mfma_kernel<64, NW, WPE, true>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+            case 128: return launch(attn_mfma_kernel<128, NW, WPE, true>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+            case 256: return launch(attn_mfma_kernel<256, 4, 1, true>, dim3(n_blocks), dim3(256), 0, s, p);
+            default: return KVCOMM_EUNSUPPORTED;
+        }
+    }
+    const unsigned n_blocks = (unsigned)p.n_items;
     switch (D) {
-        case 64: return launch(attn_mfma_kernel<64, NW, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
-        case 128: return launch(attn_mfma_kernel<128, NW, WPE>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
-        case 256: return launch(attn_mfma_kernel<256, 4, 1>, dim3(n_blocks), dim3(256), 0, s, p);
+        case 64: return launch(attn_mfma_kernel<64, NW, WPE, false>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 128: return launch(attn_mfma_kernel<128, NW, WPE, false>, dim3(n_blocks), dim3(64 * NW), 0, s, p);
+        case 256: return launch(attn_mfma_kernel<256, 4, 1, false>, dim3(n_blocks), dim3(256), 0, s, p);
         default: return KVCOMM_EUNSUPPORTED;
     }
+}
+
+}  // namespace
+
+extern "C" int kvcomm_suffix_attn(const kvcomm_model *model, kvcomm_tensor q, kvcomm_tensor cache_k,
+                                  kvcomm_tensor cache_v, int32_t n_ctx, int32_t tq, float softmax_scale,
+                                  kvcomm_tensor out, float *lse_out, void *, size_t, void *stream)
+{
+    return suffix_attn(model, q, cache_k, cache_v, n_ctx, tq, softmax_scale, out, lse_out, 0, stream);
+}
+
+extern "C" int kvcomm_suffix_attn_confined(const kvcomm_model *model, kvcomm_tensor q, kvcomm_tensor cache_k,
+                                           kvcomm_tensor cache_v, int32_t n_ctx, int32_t tq, float softmax_scale,
+                                           kvcomm_tensor out, float *lse_out, int32_t max_blocks, void *stream)
+{
+    if (max_blocks < 8) return KVCOMM_EINVAL;   // at least one block on each of the 8 XCDs
+    return suffix_attn(model, q, cache_k, cache_v, n_ctx, tq, softmax_scale, out, lse_out, max_blocks, stream);
 }

@@ -364,6 +364,18 @@ def test_align_argument_errors(lib):
     assert _align(lib, _model(dtype=0), bk=_tensor(st=2)) == EINVAL   # fp32 rows need strides in multiples of 4
 
 
+def test_suffix_attn_confined_argument_errors(lib):
+    m = _model()
+    call = lambda max_blocks=64, n_ctx=10, tq=4, q=None: lib.kvcomm_suffix_attn_confined(
+        ctypes.byref(m), q or _tensor(), _tensor(0x2000), _tensor(0x3000), n_ctx, tq, 0.0, _tensor(0x4000), None,
+        max_blocks, None)
+    for bad in (7, 0, -1):
+        assert call(max_blocks=bad) == EINVAL       # fewer than one block per XCD
+    assert call(tq=0) == EINVAL                     # the checks of kvcomm_suffix_attn come first for valid max_blocks
+    assert call(n_ctx=-1) == EINVAL
+    assert call(q=_tensor(ptr=None)) == EINVAL
+
+
 def test_suffix_attn_argument_errors(lib):
     m = _model()
     call = lambda q=None, n_ctx=10, tq=4, out=None: lib.kvcomm_suffix_attn(

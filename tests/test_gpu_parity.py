@@ -244,6 +244,37 @@ def test_attention_short_context_full_blocks(n_ctx, tq):
     check_close(to_np(out), want, w.dtype, "O")
 
 
+@pytest.mark.parametrize("max_blocks", [8, 9, 13, 24, 47, 48, 1000])
+def test_attention_confined_is_bit_identical(max_blocks):
+    """The persistent form of the attention launch (at most max_blocks thread blocks, each walking a share of the
+    work items of its XCD): same bits as the plain launch, for grids smaller than, equal to and larger than the
+    number of items (48 here: 3 layers x 2 kv heads x 8 row tiles), including grids that leave some XCD with fewer
+    blocks than others and blocks with nothing to do."""
+    w = scaled(SMALL_BF16, n_layers=3, n_kv_heads=2, n_q_heads=8, prefix_len=100, n_segments=0, tq=500)
+    say(f"attn confined max_blocks={max_blocks}")
+    model = hotpath.model_of(w)
+    agent = workloads.make_agent(w, 5, DEV)
+    out, lse = kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx, want_lse=True)
+    out2, lse2 = kv.kvcomm_suffix_attn_confined(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx, max_blocks,
+                                                want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+    if max_blocks == 13:
+        want = oracle.suffix_attn(to_np(agent.q), to_np(agent.cache_k), to_np(agent.cache_v), w.n_ctx)
+        check_close(to_np(out2), want, w.dtype, "O")
+
+
+@pytest.mark.parametrize("w", [SMALL_BF16_D64, SMALL_BF16_D256, SMALL_F32_D128], ids=lambda w: w.name)
+def test_attention_confined_other_head_dims_and_fp32(w):
+    say(f"attn confined {w.name}")
+    model = hotpath.model_of(w)
+    agent = workloads.make_agent(w, 6, DEV)
+    out = kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx)
+    out2 = kv.kvcomm_suffix_attn_confined(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx, 8)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
 # ------------------------------------------------- full-size configurations, sampled outputs
 def sample_tokens(S, seed, n_min=64):
     """At least n_min tokens of a segment: both ends, every multiple of 16 in the first and the last 128 tokens
