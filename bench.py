@@ -30,13 +30,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, TFLOP/s
 # runs of this script, each scaled by the same counter's reading for a plain 1 GiB copy
 # (profiles/bench_llama8b_5agents_hbm_traffic.md; tests/test_bench_constants.py holds the two together).
 # Not measured live: counters need the profiler.
-HBM_TRAFFIC_READ_WRITTEN = {"align_kv": (2416128819, 268435456),                           # align_kernel
-                            "anchor_weights": (1208154522 + 8502477, 8389734 + 82022),     # dist_partial_kernel + finalize_kernel
-                            "suffix_attn": (537205146, 136314880)}                         # attn_mfma_kernel
+HBM_TRAFFIC_READ_WRITTEN = {"align_kv": (2416182477, 268435456),                           # align_kernel
+                            "anchor_weights": (1208184422 + 8502272, 8390349 + 82022),     # dist_partial_kernel + finalize_kernel
+                            "suffix_attn": (537208422, 136314880)}                         # attn_mfma_kernel
 HBM_TRAFFIC_BYTES = {k: r + w for k, (r, w) in HBM_TRAFFIC_READ_WRITTEN.items()}
 # Share of the kernel's cycles in which a SIMD's matrix pipe is busy (SQ_VALU_MFMA_BUSY_CYCLES per SIMD over
 # GRBM_GUI_ACTIVE per XCD, profiles/suffix_attn_llama8b_5agents_mfma_counters.md); not measured live either.
-SUFFIX_ATTN_MFMA_BUSY_FRAC = 0.606
+SUFFIX_ATTN_MFMA_BUSY_FRAC = 0.599
 
 
 def cpu_baseline(w):
@@ -95,7 +95,7 @@ def _stats(events):
 
 
 def config_steps(torch, kv, dev, names=("pool_scaling_a4", "pool_scaling_a16", "pool_scaling_a32", "pool_scaling_a64",
-                                        "long_context", "llama70b"), steps=4, warmup=2):
+                                        "long_context", "llama70b"), steps=4, warmup=2, streams=None):
     """Whole steps of the other baseline configurations, in the launch configuration of the timed region: per agent
     one batched weights call, one batched align call into the agent's cache and the suffix attention.  One agent's
     inputs are generated and every agent of the step runs on them (an agent's pass streams several GB, far beyond
@@ -159,10 +159,74 @@ def config_steps(torch, kv, dev, names=("pool_scaling_a4", "pool_scaling_a16", "
             mean, med = _stats(ev["attn"])
             r["attn"] = {"avg_call_ms": mean, "median_call_ms": med, "tflops": one.attn_flops() / mean / 1e9,
                          "frac_of_mfma_peak": one.attn_flops() / mean / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        if w.tq and w.n_agents >= 2 and streams is not None:
+            r["two_stream"] = two_stream_config_step(torch, kv, w, model, streams, [(ag, out, sc, wjobs, ajobs)], dev, ms)
         res[name] = r
         del ag, out, sc, wjobs, ajobs
         torch.cuda.empty_cache()
     return res
+
+
+def two_stream_config_step(torch, kv, w, model, streams, sets, dev, sequential_ms, steps=3):
+    """The same step of a configuration on two streams: weights + alignment of the next agent beside the attention
+    of the current one, the attention confined to a share of the compute units (kvcomm_suffix_attn_confined).  Two
+    sets of agent buffers alternate (the alignment overwrites the cache slots the attention reads).  The share is
+    the best of a few candidates, each tried for one step."""
+    from paper_2510_12872_amd import hotpath, workloads
+
+    ag = workloads.make_agent(w, 1, dev)
+    sc = hotpath.AgentScratch(model, [w.seg_len] * w.n_segments, [w.n_anchors] * w.n_segments, kv.W_TOKEN, dev)
+    wjobs = [dict(seg_base_k=seg.base_k, anchor_base_k=seg.anchor_k, anchor_len=seg.anchor_len,
+                  weights_out=sc.weights[j], nearest_out=sc.nearest[j], selected_out=sc.selected[j])
+             for j, seg in enumerate(ag.segments)]
+    ajobs = [dict(base_k=seg.base_k, base_v=seg.base_v, anchor_dk=seg.anchor_dk, anchor_dv=seg.anchor_dv,
+                  anchor_len=seg.anchor_len, weights=sc.weights[j], delta_pos=seg.delta_pos,
+                  anchor_delta_pos=seg.anchor_delta_pos,
+                  out_k=ag.cache_k[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len],
+                  out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len])
+             for j, seg in enumerate(ag.segments)]
+    sets = sets + [(ag, torch.empty_like(ag.q), sc, wjobs, ajobs)]
+    s_align, s_attn = streams
+    done = [None, None]
+    count = [0]
+
+    def run(n_steps, blocks):
+        cur = torch.cuda.current_stream()
+        s_align.wait_stream(cur)
+        s_attn.wait_stream(cur)
+        for _ in range(n_steps * w.n_agents):
+            b = count[0] % 2
+            count[0] += 1
+            a, o, scr, wj, aj = sets[b]
+            with torch.cuda.stream(s_align):
+                if done[b] is not None:
+                    s_align.wait_event(done[b])
+                kv.kvcomm_anchor_weights_batch(model, wj, w.temperature, kv.W_TOKEN, workspace=scr.workspace)
+                kv.kvcomm_align_kv_batch(model, aj, kv.W_TOKEN)
+                aligned = torch.cuda.Event()
+                aligned.record(s_align)
+            with torch.cuda.stream(s_attn):
+                s_attn.wait_event(aligned)
+                kv.kvcomm_suffix_attn_confined(model, a.q, a.cache_k, a.cache_v, w.n_ctx, blocks, out=o)
+                done[b] = torch.cuda.Event()
+                done[b].record(s_attn)
+        cur.wait_stream(s_align)
+        cur.wait_stream(s_attn)
+
+    def timed(n_steps, blocks):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run(n_steps, blocks)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n_steps * 1e3
+
+    run(1, 160)
+    trials = {blocks: timed(1, blocks) for blocks in (160, 152, 144, 136)}
+    best = min(trials, key=trials.get)
+    ms = timed(steps, best)
+    return {"ms_per_step": ms, "tokens_per_s": w.aligned_tokens / (ms * 1e-3), "attn_blocks": best,
+            "gain_over_sequential": sequential_ms / ms - 1.0,
+            "trial_ms_per_step": {str(k): v for k, v in trials.items()}}
 
 
 def compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs, steps=5, warmup=2):
@@ -492,7 +556,9 @@ def main():
         return
     if args.configs_only:
         names = args.config_names.split(",") if args.config_names else None
-        print(json.dumps({"configs": config_steps(torch, kv, dev, names) if names else config_steps(torch, kv, dev)}))
+        pair = (torch.cuda.Stream(), torch.cuda.Stream())   # the first two streams of a process do not share a queue
+        print(json.dumps({"configs": config_steps(torch, kv, dev, names, streams=pair) if names
+                          else config_steps(torch, kv, dev, streams=pair)}))
         return
     w = workloads.LLAMA8B_5AGENTS
     model = hotpath.model_of(w)
@@ -706,7 +772,7 @@ def main():
         result["compressed_deviations"] = compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs)
         agents.clear(), outs.clear(), scratches.clear(), wjobs.clear(), ajobs.clear()   # config 5 needs the room
         torch.cuda.empty_cache()
-        result["configs"] = config_steps(torch, kv, dev)
+        result["configs"] = config_steps(torch, kv, dev, streams=(s_align, s_attn) if overlap_ms is not None else None)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)
