@@ -13,4 +13,4 @@ extern "C" const char *kvcomm_status_string(int status)
     }
 }
 
-extern "C" int kvcomm_version(void) { return 120; }
+extern "C" int kvcomm_version(void) { return 200; }  // 0.2.0: batched 8-bit update, static-scratch weights, confined attention
