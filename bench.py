@@ -186,32 +186,18 @@ def two_stream_config_step(torch, kv, w, model, streams, sets, dev, sequential_m
                   out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len])
              for j, seg in enumerate(ag.segments)]
     sets = sets + [(ag, torch.empty_like(ag.q), sc, wjobs, ajobs)]
-    s_align, s_attn = streams
-    done = [None, None]
+    pipe = hotpath.TwoStreamPipeline(model, w.temperature, 160, align_stream=streams[0], attn_stream=streams[1])
     count = [0]
 
     def run(n_steps, blocks):
-        cur = torch.cuda.current_stream()
-        s_align.wait_stream(cur)
-        s_attn.wait_stream(cur)
+        pipe.attn_blocks = blocks
+        pipe.fork()
         for _ in range(n_steps * w.n_agents):
             b = count[0] % 2
             count[0] += 1
             a, o, scr, wj, aj = sets[b]
-            with torch.cuda.stream(s_align):
-                if done[b] is not None:
-                    s_align.wait_event(done[b])
-                kv.kvcomm_anchor_weights_batch(model, wj, w.temperature, kv.W_TOKEN, workspace=scr.workspace)
-                kv.kvcomm_align_kv_batch(model, aj, kv.W_TOKEN)
-                aligned = torch.cuda.Event()
-                aligned.record(s_align)
-            with torch.cuda.stream(s_attn):
-                s_attn.wait_event(aligned)
-                kv.kvcomm_suffix_attn_confined(model, a.q, a.cache_k, a.cache_v, w.n_ctx, blocks, out=o)
-                done[b] = torch.cuda.Event()
-                done[b].record(s_attn)
-        cur.wait_stream(s_align)
-        cur.wait_stream(s_attn)
+            pipe.submit(b, wj, aj, scr.workspace, a.q, a.cache_k, a.cache_v, w.n_ctx, o)
+        pipe.join()
 
     def timed(n_steps, blocks):
         torch.cuda.synchronize()
@@ -609,69 +595,24 @@ def main():
             timed("attn", record, lambda: kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
                                                                 out=outs[ai]))
 
-    # HIP maps streams onto a few hardware queues, and two streams that share a queue run one after the other:
-    # the two-stream step keeps the alignment on the first stream and picks for the attention, by a short trial,
-    # the candidate that really runs beside it.
-    s_align = torch.cuda.Stream()
-    attn_candidates = [torch.cuda.Stream() for _ in range(3)]
-    s_attn = attn_candidates[0]
-    attn_done = [None] * len(agents)
-
-    def step_overlapped():
-        # The memory-bound alignment of the next agent runs beside the matrix-core-bound attention of the
-        # current one.  The attention is launched as at most --attn-blocks persistent blocks (one per CU), so
-        # that the rest of the chip is free for the alignment kernels.  An event per agent orders attention behind
-        # its own alignment, another one the next step's alignment behind this step's attention of the same
-        # agent (it overwrites the cache slots the attention reads); steps are not separated otherwise.
-        for ai, ag in enumerate(agents):
-            with torch.cuda.stream(s_align):
-                if attn_done[ai] is not None:
-                    s_align.wait_event(attn_done[ai])
-                kv.kvcomm_anchor_weights_batch(model, wjobs[ai], w.temperature, kv.W_TOKEN,
-                                               workspace=scratches[ai].workspace)
-                kv.kvcomm_align_kv_batch(model, ajobs[ai], kv.W_TOKEN)
-                aligned = torch.cuda.Event()
-                aligned.record(s_align)
-            with torch.cuda.stream(s_attn):
-                s_attn.wait_event(aligned)
-                if args.attn_blocks > 0:
-                    kv.kvcomm_suffix_attn_confined(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, args.attn_blocks,
-                                                   out=outs[ai])
-                else:
-                    kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx, out=outs[ai])
-                attn_done[ai] = torch.cuda.Event()
-                attn_done[ai].record(s_attn)
+    # Two-stream form of the step: weights + alignment of the next agent beside the attention of the current one,
+    # the attention confined to --attn-blocks compute units (hotpath.TwoStreamPipeline).
+    pipe = hotpath.TwoStreamPipeline(model, w.temperature, args.attn_blocks)
 
     def overlapped_steps(n):
-        cur = torch.cuda.current_stream()
-        s_align.wait_stream(cur)
-        s_attn.wait_stream(cur)
+        pipe.fork()
         for _ in range(n):
-            step_overlapped()
-        cur.wait_stream(s_align)
-        cur.wait_stream(s_attn)
-
-    def pick_attention_stream():
-        nonlocal s_attn
-        best = None
-        for cand in attn_candidates:
-            s_attn = cand
-            overlapped_steps(2)
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            overlapped_steps(3)
-            torch.cuda.synchronize()
-            t = time.perf_counter() - t
-            if best is None or t < best[0]:
-                best = (t, cand)
-        s_attn = best[1]
+            for ai, ag in enumerate(agents):
+                pipe.submit(ai, wjobs[ai], ajobs[ai], scratches[ai].workspace, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
+                            outs[ai])
+        pipe.join()
 
     for _ in range(args.warmup):
         step(False)
     if args.overlap:
         for _ in range(5):               # per-kernel durations, one kernel on the chip at a time
             step(not args.no_events)
-        pick_attention_stream()
+        pipe.pick_attention_stream(overlapped_steps)
         overlapped_steps(3)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -688,7 +629,7 @@ def main():
         # For information, after the timed region: the same steps with the next agent's alignment beside the
         # attention of the current one (two streams).  `value` and the rooflines above do not use it.
         n_ov = max(1, min(args.steps, 30))
-        pick_attention_stream()
+        pipe.pick_attention_stream(overlapped_steps)
         overlapped_steps(5)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -772,7 +713,7 @@ def main():
         result["compressed_deviations"] = compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs)
         agents.clear(), outs.clear(), scratches.clear(), wjobs.clear(), ajobs.clear()   # config 5 needs the room
         torch.cuda.empty_cache()
-        result["configs"] = config_steps(torch, kv, dev, streams=(s_align, s_attn) if overlap_ms is not None else None)
+        result["configs"] = config_steps(torch, kv, dev, streams=(pipe.s_align, pipe.s_attn) if overlap_ms is not None else None)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)

@@ -101,3 +101,76 @@ def reuse_agent(w, model, agent, out=None, gran=kv.W_TOKEN, scratches=None, stre
     if agent.q is None:
         return None
     return kv.kvcomm_suffix_attn(model, agent.q, agent.cache_k, agent.cache_v, w.n_ctx, out=out, stream=stream)
+
+
+class TwoStreamPipeline:
+    """The reuse step of consecutive agents on two streams: weights + alignment of an agent run beside the
+    attention of the agent before it.  The attention is launched through kvcomm_suffix_attn_confined as at most
+    `attn_blocks` persistent blocks, so that the other compute units are free for the memory-bound alignment
+    kernels for the whole launch (attn_blocks = 0: the plain launch, which leaves them only the gaps).
+
+    Ordering: an event per submission puts the attention behind its own alignment; a second one, kept per buffer
+    key, puts the next alignment into the same cache behind the attention that still reads it.  HIP maps streams
+    onto a few hardware queues and two streams that share one run one after the other: pick_attention_stream()
+    tries candidates and keeps the fastest."""
+
+    def __init__(self, model, temperature=1.0, attn_blocks=160, gran=kv.W_TOKEN, align_stream=None, attn_stream=None):
+        self.model, self.temperature, self.attn_blocks, self.gran = model, temperature, attn_blocks, gran
+        self.s_align = align_stream or torch.cuda.Stream()
+        self.s_attn = attn_stream or torch.cuda.Stream()
+        self._done = {}
+
+    def fork(self):
+        """Both streams wait for the work already queued on the current stream."""
+        cur = torch.cuda.current_stream()
+        self.s_align.wait_stream(cur)
+        self.s_attn.wait_stream(cur)
+
+    def join(self):
+        """The current stream waits for everything submitted so far."""
+        cur = torch.cuda.current_stream()
+        cur.wait_stream(self.s_align)
+        cur.wait_stream(self.s_attn)
+
+    def submit(self, key, wjobs, ajobs, workspace, q, cache_k, cache_v, n_ctx, out, q8=False):
+        """One agent: batched weights and alignment (job lists as for the batched calls) on the alignment stream,
+        then its suffix attention on the attention stream.  `key` names the agent's buffers."""
+        with torch.cuda.stream(self.s_align):
+            if key in self._done:
+                self.s_align.wait_event(self._done[key])
+            kv.kvcomm_anchor_weights_batch(self.model, wjobs, self.temperature, self.gran, workspace=workspace)
+            if q8:
+                kv.kvcomm_align_kv_q8_batch(self.model, ajobs, self.gran)
+            else:
+                kv.kvcomm_align_kv_batch(self.model, ajobs, self.gran)
+            aligned = torch.cuda.Event()
+            aligned.record(self.s_align)
+        with torch.cuda.stream(self.s_attn):
+            self.s_attn.wait_event(aligned)
+            if q is not None:
+                if self.attn_blocks > 0:
+                    kv.kvcomm_suffix_attn_confined(self.model, q, cache_k, cache_v, n_ctx, self.attn_blocks, out=out)
+                else:
+                    kv.kvcomm_suffix_attn(self.model, q, cache_k, cache_v, n_ctx, out=out)
+            done = torch.cuda.Event()
+            done.record(self.s_attn)
+            self._done[key] = done
+
+    def pick_attention_stream(self, run_steps, candidates=None, warm=2, timed=3):
+        """run_steps(n) must submit n steps through this pipeline (fork ... join).  Tries every candidate stream
+        for the attention and keeps the one with the shortest steps."""
+        import time
+        candidates = candidates or [self.s_attn] + [torch.cuda.Stream() for _ in range(2)]
+        best = None
+        for cand in candidates:
+            self.s_attn = cand
+            run_steps(warm)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            run_steps(timed)
+            torch.cuda.synchronize()
+            t = time.perf_counter() - t
+            if best is None or t < best[0]:
+                best = (t, cand)
+        self.s_attn = best[1]
+        return best[1]

@@ -275,6 +275,62 @@ def test_attention_confined_other_head_dims_and_fp32(w):
     assert torch.equal(out, out2)
 
 
+def test_two_stream_pipeline_equals_sequential_steps():
+    """hotpath.TwoStreamPipeline (weights + alignment of the next agent beside the confined attention of the current
+    one; two buffer sets; several steps, the inputs of every step different) against the same calls on one stream:
+    bit-identical outputs for every agent of every step, i.e. the events order every read behind its write."""
+    w = scaled(SMALL_BF16, n_layers=3, n_agents=2, seg_len=128, n_segments=2, prefix_len=40, tq=300)
+    say("two-stream pipeline")
+    model = hotpath.model_of(w)
+    agents = [workloads.make_agent(w, a, DEV) for a in range(2)]
+    scr = [hotpath.AgentScratch(model, [w.seg_len] * w.n_segments, [w.n_anchors] * w.n_segments, kv.W_TOKEN, DEV)
+           for _ in agents]
+
+    def jobs(ai):
+        ag, sc = agents[ai], scr[ai]
+        wj = [dict(seg_base_k=s.base_k, anchor_base_k=s.anchor_k, anchor_len=s.anchor_len, weights_out=sc.weights[j],
+                   nearest_out=sc.nearest[j], selected_out=sc.selected[j]) for j, s in enumerate(ag.segments)]
+        aj = [dict(base_k=s.base_k, base_v=s.base_v, anchor_dk=s.anchor_dk, anchor_dv=s.anchor_dv,
+                   anchor_len=s.anchor_len, weights=sc.weights[j], delta_pos=s.delta_pos,
+                   anchor_delta_pos=s.anchor_delta_pos,
+                   out_k=ag.cache_k[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len],
+                   out_v=ag.cache_v[:, :, w.seg_offset(j):w.seg_offset(j) + w.seg_len])
+              for j, s in enumerate(ag.segments)]
+        return wj, aj
+
+    J = [jobs(0), jobs(1)]
+    n_steps = 4
+    base0 = [[s.base_k.clone() for s in ag.segments] for ag in agents]
+
+    def set_inputs(step):   # every step works on different base keys, so a stale read would show
+        for ai, ag in enumerate(agents):
+            for j, s in enumerate(ag.segments):
+                s.base_k.copy_(base0[ai][j] * (1.0 + 0.25 * step))
+
+    # sequential reference: one stream, synchronised step by step
+    want = []
+    for step in range(n_steps):
+        set_inputs(step)
+        for ai, ag in enumerate(agents):
+            kv.kvcomm_anchor_weights_batch(model, J[ai][0], w.temperature, kv.W_TOKEN, workspace=scr[ai].workspace)
+            kv.kvcomm_align_kv_batch(model, J[ai][1], kv.W_TOKEN)
+            want.append(kv.kvcomm_suffix_attn(model, ag.q, ag.cache_k, ag.cache_v, w.n_ctx).clone())
+        torch.cuda.synchronize()
+    for blocks in (8, 11, 0):
+        pipe = hotpath.TwoStreamPipeline(model, w.temperature, attn_blocks=blocks)
+        outs = [torch.empty_like(agents[0].q) for _ in range(n_steps * 2)]
+        for step in range(n_steps):
+            set_inputs(step)          # on the current stream; fork() puts the pipeline behind it
+            pipe.fork()
+            for ai, ag in enumerate(agents):
+                pipe.submit(ai, J[ai][0], J[ai][1], scr[ai].workspace, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
+                            outs[2 * step + ai])
+            pipe.join()               # the next step's inputs are written behind this step's reads
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(outs, want)):
+            assert torch.equal(got, ref), f"attn_blocks {blocks}: step {i // 2} agent {i % 2}"
+
+
 # ------------------------------------------------- full-size configurations, sampled outputs
 def sample_tokens(S, seed, n_min=64):
     """At least n_min tokens of a segment: both ends, every multiple of 16 in the first and the last 128 tokens
