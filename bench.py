@@ -215,7 +215,7 @@ def two_stream_config_step(torch, kv, w, model, streams, sets, dev, sequential_m
             "trial_ms_per_step": {str(k): v for k, v in trials.items()}}
 
 
-def compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs, steps=5, warmup=2):
+def compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs, steps=5, warmup=2, pipe=None):
     """The timed region's step with every anchor's deviations stored as E4M3 (one byte per element, scale 2^-10):
     batched weights, batched compressed update, attention."""
     scale = 2.0 ** -10
@@ -256,7 +256,23 @@ def compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs, steps=5
     mean, med = _stats(ev)
     rows = w.n_layers * w.n_kv_heads * w.n_segments * w.seg_len          # per launch: the segments of one agent
     nbytes = rows * w.head_dim * (4 * 2 + 2 * w.n_anchors)
+    two_stream = None
+    if pipe is not None:     # the same step on two streams (see hotpath.TwoStreamPipeline)
+        def run(n):
+            pipe.fork()
+            for _ in range(n):
+                for ai, ag in enumerate(agents):
+                    pipe.submit(ai, wjobs[ai], qjobs[ai], scratches[ai].workspace, ag.q, ag.cache_k, ag.cache_v, w.n_ctx,
+                                outs[ai], q8=True)
+            pipe.join()
+        run(3)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        run(10)
+        torch.cuda.synchronize()
+        two_stream = (time.perf_counter() - t1) / 10 * 1e3
     return {"ms_per_step": ms, "tokens_per_s": w.aligned_tokens / (ms * 1e-3),
+            "two_stream_ms_per_step": two_stream,
             "align_kv_q8_batch": {"avg_call_ms": mean, "median_call_ms": med, "algorithmic_bytes": nbytes,
                                   "GBps": nbytes / mean / 1e6, "frac_of_hbm_peak": nbytes / mean / 1e6 / HBM_PEAK_GBS},
             "note": "deviations stored as E4M3 x 2^-10 (lossy); same weights and attention calls as the timed region"}
@@ -710,7 +726,8 @@ def main():
     if not args.no_extras and not args.overlap:
         # After the timed region, for the record: the same step on compressed deviations, then whole steps of the
         # other baseline configurations (3: pool scaling, 4: long context, 5: 70B shape).
-        result["compressed_deviations"] = compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs)
+        result["compressed_deviations"] = compressed_step(torch, kv, w, model, agents, outs, scratches, wjobs,
+                                                          pipe=pipe if overlap_ms is not None else None)
         agents.clear(), outs.clear(), scratches.clear(), wjobs.clear(), ajobs.clear()   # config 5 needs the room
         torch.cuda.empty_cache()
         result["configs"] = config_steps(torch, kv, dev, streams=(pipe.s_align, pipe.s_attn) if overlap_ms is not None else None)

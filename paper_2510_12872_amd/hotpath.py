@@ -1,8 +1,9 @@
-"""Host-side sequencing of the reuse step for one agent: three library calls per segment/agent.
+"""Host-side sequencing of the reuse step: three library calls per segment/agent.
 
 Nothing is computed here; the functions only issue the calls of include/kvcomm.h in the
 order of the reuse branch of Algorithm 1 (weights -> offset approximation per placeholder,
-then attention over the concatenated cache) on the current stream.
+then attention over the concatenated cache), on the current stream or, for consecutive
+agents, on two streams (TwoStreamPipeline).
 """
 import torch
 
